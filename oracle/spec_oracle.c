@@ -1,0 +1,364 @@
+/*
+ * CPU oracle for the target-side verification step of hybrid ordinary-parallel
+ * speculative serving (paper: Method, "Target-Side Adaptive Hybrid Policy";
+ * Appendix "Implementation Details", subsection "Target side").
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, fp64 restatement of what
+ * the four calls of the verification step compute.  It shares no code, header,
+ * table or helper with the GPU library, is never linked into it, and must only
+ * be called from tests, the smoke check and the cpu_baseline leg of the
+ * benchmark.  No blocking, no fusion, no online softmax: every function is the
+ * textbook definition (attention, matmul, argmax, prefix match, page-table
+ * truncation) or the canonical speculative rejection-sampling procedure the
+ * paper names (Fig. "Illustration of SPECTRE decoding": the target verifies
+ * drafts via rejection sampling; Related Work: canonical rejection sampling
+ * preserves the target distribution), taken step by step.
+ *
+ * Notation (paper, Appendix "Target side"): request i has a committed prefix
+ * of c_i tokens, gamma_i draft tokens d_1..d_gamma, and the verification
+ * candidate y = [b, d_1, ..., d_gamma] with b the last committed (bonus)
+ * token, so n_i = gamma_i + 1 rows are scored; qo_indptr[i] is the first row
+ * of request i in the merged batch Y_n.  gamma_i = 0 is the padded
+ * parallel-mode / one-token-decode candidate (eq. parallel_rollback_pad and
+ * the "Fallback" paragraph): a single row, ordinary decoding.
+ *
+ * All pointers are host pointers.  bf16 values are passed as uint16_t bit
+ * patterns.  Return value 0 = ok, negative = bad argument.
+ *
+ * Pinned by tests/test_oracle_*.py (prefix-match, q == p, gamma = 0 decode,
+ * tiny-vocabulary exact distribution, Philox known answers, page
+ * conservation, textbook matmul/softmax special cases).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_EINVAL (-1)
+
+static float bf16_bits_to_float(uint16_t h) {
+    uint32_t u = ((uint32_t)h) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Attention over the paged KV cache for every candidate position.
+ * Row j of request i attends to key positions 0 .. c_i + j (its committed
+ * prefix plus the candidate tokens up to and including itself: causal inside
+ * the draft block).  Position t lives in physical page
+ * page_table[i][t / P] at slot t % P; cache layout [page][kv_head][slot][D].
+ * Query head h reads kv head h / (Hq / Hkv).
+ *   s_t = scale * <q, k_t>;  w_t = exp(s_t - max s);  O = sum w_t v_t / sum w_t
+ * out is fp32 [M, Hq, D]; lse (optional) = max s + log(sum w) per (row, head).
+ * ------------------------------------------------------------------------- */
+int oracle_verify_attn(const uint16_t* q, const uint16_t* k_cache, const uint16_t* v_cache,
+                       const int32_t* page_table, int max_pages_per_seq,
+                       const int32_t* seq_lens, const int32_t* qo_indptr,
+                       float* out, float* lse,
+                       int B, int M, int Hq, int Hkv, int D, int page_size, float scale)
+{
+    if (!q || !k_cache || !v_cache || !page_table || !seq_lens || !qo_indptr || !out) return ORACLE_EINVAL;
+    if (B < 0 || M < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || page_size <= 0 || Hq % Hkv) return ORACLE_EINVAL;
+    const int G = Hq / Hkv;
+    int status = ORACLE_OK;
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+    for (int i = 0; i < B; ++i) {
+        for (int h = 0; h < Hq; ++h) {
+            const int r0 = qo_indptr[i], n = qo_indptr[i + 1] - qo_indptr[i];
+            const int c = seq_lens[i];
+            const int kvh = h / G;
+            double* s = (double*)malloc(sizeof(double) * (size_t)(c + n > 0 ? c + n : 1));
+            double* acc = (double*)malloc(sizeof(double) * (size_t)D);
+            for (int j = 0; j < n; ++j) {
+                const int row = r0 + j;
+                const int nk = c + j + 1;
+                const uint16_t* qv = q + ((size_t)row * Hq + h) * D;
+                double m = -INFINITY;
+                for (int t = 0; t < nk; ++t) {
+                    const int page = page_table[(size_t)i * max_pages_per_seq + t / page_size];
+                    if (page < 0) { status = ORACLE_EINVAL; s[t] = -INFINITY; continue; }
+                    const uint16_t* kv = k_cache + (((size_t)page * Hkv + kvh) * page_size + t % page_size) * D;
+                    double dot = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        dot += (double)bf16_bits_to_float(qv[d]) * (double)bf16_bits_to_float(kv[d]);
+                    s[t] = (double)scale * dot;
+                    if (s[t] > m) m = s[t];
+                }
+                for (int d = 0; d < D; ++d) acc[d] = 0.0;
+                double denom = 0.0;
+                for (int t = 0; t < nk; ++t) {
+                    const int page = page_table[(size_t)i * max_pages_per_seq + t / page_size];
+                    if (page < 0) continue;
+                    const double w = exp(s[t] - m);
+                    denom += w;
+                    const uint16_t* vv = v_cache + (((size_t)page * Hkv + kvh) * page_size + t % page_size) * D;
+                    for (int d = 0; d < D; ++d) acc[d] += w * (double)bf16_bits_to_float(vv[d]);
+                }
+                float* o = out + ((size_t)row * Hq + h) * D;
+                for (int d = 0; d < D; ++d) o[d] = (float)(acc[d] / denom);
+                if (lse) lse[(size_t)row * Hq + h] = (float)(m + log(denom));
+            }
+            free(s);
+            free(acc);
+        }
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- *
+ * LM head: one logits row per candidate position (every position of Y_n must
+ * be scored).  logits[r][v] = sum_k hidden[r][k] * W[v][k], fp64 sum, fp32 out.
+ * ------------------------------------------------------------------------- */
+int oracle_lm_head(const uint16_t* hidden, const uint16_t* W, float* logits, int M, int H, int V)
+{
+    if (!hidden || !W || !logits || M < 0 || H <= 0 || V < 0) return ORACLE_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (long v = 0; v < V; ++v) {
+        const uint16_t* w = W + (size_t)v * H;
+        for (int r = 0; r < M; ++r) {
+            const uint16_t* x = hidden + (size_t)r * H;
+            double dot = 0.0;
+            for (int k = 0; k < H; ++k)
+                dot += (double)bf16_bits_to_float(x[k]) * (double)bf16_bits_to_float(w[k]);
+            logits[(size_t)r * V + v] = (float)dot;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+ * as 1, 2, 3", SC'11): ten rounds of two 32x32->64 multiplies with the key
+ * bumped by the Weyl constants between rounds.
+ * ------------------------------------------------------------------------- */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The uniform the acceptance rule draws: counter (0, j, tag, round), key =
+ * the two halves of the per-request seed, first output word, top 24 bits.
+ * tag 0 = accept test of draft j, tag 1 = the bonus/residual draw at row j. */
+float oracle_uniform(uint64_t seed, uint32_t round, uint32_t j, uint32_t tag)
+{
+    const uint32_t ctr[4] = {0u, j, tag, round};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t x[4];
+    oracle_philox4x32_10(ctr, key, x);
+    return (float)(x[0] >> 8) * (1.0f / 16777216.0f);
+}
+
+/* Target distribution of one logits row at temperature T (> 0):
+ * p(v) = float( exp((l_v - max l) / T) / sum_w exp((l_w - max l) / T) ), fp64
+ * inside.  Returns 0 if the row is unusable (NaN present or max not finite). */
+static int row_is_valid(const float* l, int V)
+{
+    float m = -INFINITY;
+    for (int v = 0; v < V; ++v) {
+        if (l[v] != l[v]) return 0;
+        if (l[v] > m) m = l[v];
+    }
+    return isfinite(m);
+}
+
+int oracle_target_probs(const float* l, int V, float T, float* p)
+{
+    if (!l || !p || V <= 0 || !(T > 0.0f)) return ORACLE_EINVAL;
+    if (!row_is_valid(l, V)) return ORACLE_EINVAL;
+    double m = -INFINITY;
+    for (int v = 0; v < V; ++v) if ((double)l[v] > m) m = (double)l[v];
+    double Z = 0.0;
+    for (int v = 0; v < V; ++v) Z += exp(((double)l[v] - m) / (double)T);
+    for (int v = 0; v < V; ++v) p[v] = (float)(exp(((double)l[v] - m) / (double)T) / Z);
+    return ORACLE_OK;
+}
+
+static int row_argmax(const float* l, int V)
+{
+    int best = 0;
+    for (int v = 1; v < V; ++v) if (l[v] > l[best]) best = v;   /* ties: lowest index */
+    return best;
+}
+
+/* Inverse-CDF draw from weights rho (>= 0) with uniform u in [0,1): smallest v
+ * whose running fp64 sum exceeds u * total; if rounding lets the loop run out,
+ * the last v with positive weight. */
+static int sample_from_weights(const float* rho, int V, double total, float u)
+{
+    const double t = (double)u * total;
+    double run = 0.0;
+    int last = -1;
+    for (int v = 0; v < V; ++v) {
+        run += (double)rho[v];
+        if (rho[v] > 0.0f) last = v;
+        if (run > t) return v;
+    }
+    return last;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Acceptance.  Per request i with rows r_j = qo_indptr[i] + j, j = 0..gamma_i:
+ *  T_i == 0  greedy: g_j = argmax of row j; accept d_j while d_j == g_{j-1};
+ *            the emitted bonus is g_a at the first mismatch (or g_gamma).
+ *  T_i  > 0  rejection sampling: p_j = softmax(row j / T).  For j = 1..gamma:
+ *            accept d_j iff u_j * q_j(d_j) < p_{j-1}(d_j); at the first
+ *            rejection j* draw the bonus from norm(max(0, p_{j*-1} - q_{j*}));
+ *            if nothing is rejected draw it from p_gamma.
+ *            draft_probs == NULL means the drafter is deterministic: q_j is
+ *            one-hot at d_j.
+ * Outputs: accept_len[i] = a; out_tokens[i] = [d_1..d_a, bonus, -1, ...]
+ * (row stride gamma_max + 1); rollback[i] = (a < gamma_i).
+ * A request any of whose rows holds a NaN or has a non-finite maximum yields
+ * a = 0 and bonus -1 and ORs bit 0 into *status_flags.
+ * ------------------------------------------------------------------------- */
+int oracle_accept(const float* logits, const int32_t* tokens, const float* draft_probs,
+                  const float* temperature, const uint64_t* seeds, uint32_t round,
+                  const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
+                  uint8_t* rollback, int32_t* status_flags, int B, int M, int V, int gamma_max)
+{
+    if (!logits || !tokens || !temperature || !qo_indptr || !accept_len || !out_tokens) return ORACLE_EINVAL;
+    if (B < 0 || M < 0 || V <= 0 || gamma_max < 0) return ORACLE_EINVAL;
+    int flags = 0, bad = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(|:flags) reduction(|:bad)
+    for (int i = 0; i < B; ++i) {
+        const int r0 = qo_indptr[i];
+        const int gamma = qo_indptr[i + 1] - r0 - 1;
+        int32_t* emit = out_tokens + (size_t)i * (gamma_max + 1);
+        for (int j = 0; j <= gamma_max; ++j) emit[j] = -1;
+        accept_len[i] = 0;
+        if (rollback) rollback[i] = 0;
+        if (gamma < 0 || gamma > gamma_max) { bad = 1; continue; }
+        const float T = temperature[i];
+        if (T > 0.0f && !seeds) { bad = 1; continue; }
+        int valid = 1;
+        for (int j = 0; j <= gamma; ++j) valid &= row_is_valid(logits + (size_t)(r0 + j) * V, V);
+        for (int j = 1; j <= gamma; ++j) valid &= (tokens[r0 + j] >= 0 && tokens[r0 + j] < V);
+        if (!valid || !(T >= 0.0f)) {
+            flags |= 1;
+            if (rollback) rollback[i] = (uint8_t)(gamma > 0);
+            continue;
+        }
+        int a = 0, bonus = -1;
+        if (T == 0.0f) {
+            while (a < gamma && tokens[r0 + a + 1] == row_argmax(logits + (size_t)(r0 + a) * V, V)) ++a;
+            bonus = row_argmax(logits + (size_t)(r0 + a) * V, V);
+        } else {
+            float* p = (float*)malloc(sizeof(float) * (size_t)V);
+            float* rho = (float*)malloc(sizeof(float) * (size_t)V);
+            int rejected_at = 0;                       /* j* (1-based), 0 = none */
+            for (int j = 1; j <= gamma; ++j) {
+                oracle_target_probs(logits + (size_t)(r0 + j - 1) * V, V, T, p);
+                const int d = tokens[r0 + j];
+                const float qd = draft_probs ? draft_probs[(size_t)(r0 - i + j - 1) * V + d] : 1.0f;
+                const float u = oracle_uniform(seeds[i], round, (uint32_t)j, 0u);
+                if ((float)((double)u * (double)qd) < p[d]) { ++a; }
+                else { rejected_at = j; break; }
+            }
+            if (rejected_at) {
+                /* p still holds p_{j*-1} */
+                const int d = tokens[r0 + rejected_at];
+                const float* qrow = draft_probs ? draft_probs + (size_t)(r0 - i + rejected_at - 1) * V : NULL;
+                double total = 0.0;
+                for (int v = 0; v < V; ++v) {
+                    const float qv = qrow ? qrow[v] : (v == d ? 1.0f : 0.0f);
+                    const float diff = p[v] - qv;
+                    rho[v] = diff > 0.0f ? diff : 0.0f;
+                    total += (double)rho[v];
+                }
+                if (!(total > 0.0)) {              /* p == q numerically: fall back to p */
+                    total = 0.0;
+                    for (int v = 0; v < V; ++v) { rho[v] = p[v]; total += (double)p[v]; }
+                }
+                bonus = sample_from_weights(rho, V, total, oracle_uniform(seeds[i], round, (uint32_t)rejected_at, 1u));
+            } else {
+                oracle_target_probs(logits + (size_t)(r0 + gamma) * V, V, T, p);
+                double total = 0.0;
+                for (int v = 0; v < V; ++v) total += (double)p[v];
+                bonus = sample_from_weights(p, V, total, oracle_uniform(seeds[i], round, (uint32_t)(gamma + 1), 1u));
+            }
+            free(p);
+            free(rho);
+        }
+        accept_len[i] = a;
+        for (int j = 0; j < a; ++j) emit[j] = tokens[r0 + j + 1];
+        emit[a] = bonus;
+        if (rollback) rollback[i] = (uint8_t)(a < gamma);
+    }
+    if (status_flags) *status_flags |= flags;
+    return bad ? ORACLE_EINVAL : ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Commit (Appendix "Target side": p_{n+1} = Commit(p_n, y_n, L_n); only
+ * verified tokens enter the committed prefix) on the KV side.  Before the
+ * step request i owns ceil((c_i + n_i) / P) pages (the candidate's K/V were
+ * written at positions c_i .. c_i + gamma_i).  Afterwards its length is
+ * c_i + a_i + 1 (accepted drafts plus the row that produced the bonus; the
+ * bonus token's own K/V is written by the next step) and every page beyond
+ * ceil(new_len / P) is unmapped (-1) and pushed on the free list, requests in
+ * ascending order, logical pages in ascending order.
+ * ------------------------------------------------------------------------- */
+int oracle_kv_commit(int32_t* page_table, int max_pages_per_seq, int32_t* seq_lens,
+                     const int32_t* qo_indptr, const int32_t* accept_len,
+                     int32_t* free_list, int32_t free_capacity, int32_t* free_count,
+                     int B, int page_size)
+{
+    if (!page_table || !seq_lens || !qo_indptr || !accept_len || !free_list || !free_count) return ORACLE_EINVAL;
+    if (B < 0 || page_size <= 0 || max_pages_per_seq < 0) return ORACLE_EINVAL;
+    int status = ORACLE_OK;
+    for (int i = 0; i < B; ++i) {
+        const int n = qo_indptr[i + 1] - qo_indptr[i];
+        const int c = seq_lens[i];
+        int a = accept_len[i];
+        if (a < 0) a = 0;
+        if (a > n - 1) a = n - 1;
+        const int new_len = c + a + 1;
+        const int had = (c + n + page_size - 1) / page_size;
+        const int keep = (new_len + page_size - 1) / page_size;
+        for (int pg = keep; pg < had && pg < max_pages_per_seq; ++pg) {
+            int32_t* slot = page_table + (size_t)i * max_pages_per_seq + pg;
+            if (*slot >= 0) {
+                if (*free_count < free_capacity) free_list[(*free_count)++] = *slot;
+                else status = ORACLE_EINVAL;
+                *slot = -1;
+            }
+        }
+        seq_lens[i] = new_len;
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Rollback ratio and the mode threshold (Section "Throughput-Guided Hybrid
+ * Coordination", eq. r_threshold; Method, eq. mode_switch_batch).
+ * ------------------------------------------------------------------------- */
+double oracle_thr_ordinary(double B, double L, double gamma, double T_D, double T_T)
+{
+    return B * L / (T_T + (gamma - 1.0) * T_D);
+}
+
+double oracle_thr_parallel(double B, double L, double r, double T_T)
+{
+    return B * (r + (1.0 - r) * L) / T_T;
+}
+
+double oracle_r_star(double L, double gamma, double T_D, double T_T)
+{
+    return (gamma - 1.0) * L * T_D / ((T_T + (gamma - 1.0) * T_D) * (L - 1.0));
+}
