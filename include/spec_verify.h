@@ -1,0 +1,175 @@
+/*
+ * libspecverify — the target-side verification step of hybrid ordinary-parallel
+ * speculative serving, as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * One decoding round on the target server (paper, Appendix "Implementation
+ * Details", "Target side"): the batch Y_n = {y^(i)} of verification candidates
+ * y^(i) = [b, d_1 .. d_gamma_i] is scored in one pass, the accepted length L
+ * is computed per request, and the verified tokens are committed.  The four
+ * calls below are that pass for one attention layer plus the LM head:
+ *
+ *   spec_verify_attn  attention of every candidate position over the paged KV
+ *   spec_lm_head      one logits row per candidate position
+ *   spec_accept       greedy prefix match or rejection sampling -> L, bonus
+ *   spec_kv_commit    Commit on the KV side: new length, rejected pages freed
+ *
+ * Conventions for every call
+ *   - All pointers are DEVICE pointers into caller-owned memory unless the
+ *     comment says "host".  The library never allocates, frees or keeps them.
+ *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as
+ *     void*); it never synchronises with the host.  `workspace` is scratch
+ *     with no state carried between calls; it must be 256-byte aligned.
+ *   - Return value: SPEC_OK (0) or a negative code; spec_last_error_string()
+ *     gives the reason for the calling thread's last failure.  A failing call
+ *     has enqueued nothing.
+ *   - Data errors only the device can see (a page id out of range, a length
+ *     beyond the stated bound, a non-finite logits row, a token id outside the
+ *     vocabulary) never fault: the offending request is skipped or produces
+ *     the documented neutral output and a bit is OR-ed into *status_flags
+ *     (nullable, int32, device).
+ *   - Request i has c_i = seq_lens[i] committed tokens and n_i =
+ *     qo_indptr[i+1] - qo_indptr[i] = gamma_i + 1 >= 1 candidate rows; row
+ *     qo_indptr[i] + j is candidate position j.  gamma_i = 0 is ordinary
+ *     one-token decoding (the padded parallel-mode candidate of eq.
+ *     parallel_rollback_pad / the "Fallback" paragraph).
+ *   - bf16 = IEEE bfloat16 bit patterns (uint16_t storage).
+ */
+#ifndef SPEC_VERIFY_H
+#define SPEC_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPEC_OK 0
+#define SPEC_EINVAL (-1)      /* NULL pointer, negative size, misaligned workspace */
+#define SPEC_ESHAPE (-2)      /* shape outside what the kernels are built for */
+#define SPEC_EWORKSPACE (-3)  /* workspace smaller than the *_workspace_bytes() answer */
+#define SPEC_EHIP (-4)        /* the HIP runtime refused a launch */
+
+/* bits of *status_flags */
+#define SPEC_FLAG_BAD_PAGE 1      /* page id < 0 or >= num_pages met inside a visible range */
+#define SPEC_FLAG_BAD_LENGTH 2    /* c_i + n_i > max_kv_len, n_i < 1 or n_i > max_q_len */
+#define SPEC_FLAG_BAD_LOGITS 4    /* NaN in a logits row or a row maximum that is not finite */
+#define SPEC_FLAG_BAD_TOKEN 8     /* draft token id outside [0, V) */
+#define SPEC_FLAG_FREE_OVERFLOW 16 /* free list capacity exceeded in spec_kv_commit */
+#define SPEC_FLAG_NO_SEED 32      /* temperature > 0 but seeds == NULL */
+
+/* Text of the calling thread's last error ("" if none). host. */
+const char* spec_last_error_string(void);
+
+/* Library version, major * 1000 + minor. host. */
+int spec_version(void);
+
+/* Benchmark hook (host): overrides a launch heuristic; never changes results beyond fp32 summation
+ * order.  key "attn_chunk": keys per kv split of spec_verify_attn, 0 = automatic. */
+int spec_set_tuning(const char* key, int value);
+
+/* ---------------------------------------------------------------------------
+ * spec_verify_attn — ragged multi-query paged attention over the candidates
+ * (the target model's pass over Y_n, Method "Execution in ordinary/parallel
+ * mode": the target performs the verification pass on the merged batch).
+ *
+ * For request i, candidate position j, query head h:
+ *   out[row, h, :] = softmax_t( scale * <q[row, h, :], K_t> ) . V_t   over key
+ *   positions t = 0 .. c_i + j   (causal inside the candidate block),
+ * where position t of request i is slot t % page_size of physical page
+ * page_table[i * max_pages_per_seq + t / page_size], and query head h reads
+ * kv head h / (Hq / Hkv).  The K/V of the n_i candidate tokens must already be
+ * in the cache at positions c_i .. c_i + gamma_i.
+ *
+ *   q        [M, Hq, D] bf16          out  [M, Hq, D] bf16
+ *   k_cache  [num_pages, Hkv, page_size, D] bf16 (same for v_cache)
+ *   page_table [B, max_pages_per_seq] int32     seq_lens [B] int32 (c_i)
+ *   qo_indptr  [B+1] int32                      lse [M, Hq] fp32 or NULL:
+ *                                                natural-log sum-exp of the scaled scores
+ * Host bounds the launch is sized from: max_kv_len >= max_i(c_i + n_i),
+ * max_q_len >= max_i n_i.  Built for D = 128, page_size = 16, Hq % Hkv == 0,
+ * Hq / Hkv <= 64; anything else is SPEC_ESHAPE.  fp32 accumulation.
+ * Requests that break a bound are skipped (rows left untouched) and flagged.
+ * ------------------------------------------------------------------------- */
+size_t spec_verify_attn_workspace_bytes(int B, int M, int Hq, int Hkv, int D, int max_kv_len, int max_q_len);
+
+int spec_verify_attn(const void* q, const void* k_cache, const void* v_cache,
+                     const int32_t* page_table, int max_pages_per_seq, int num_pages,
+                     const int32_t* seq_lens, const int32_t* qo_indptr,
+                     void* out, float* lse,
+                     int B, int M, int Hq, int Hkv, int D, int page_size,
+                     int max_kv_len, int max_q_len, float scale,
+                     int32_t* status_flags,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * spec_lm_head — logits of every candidate position (each position of Y_n is
+ * scored so the accepted length can be computed; Appendix "Target side").
+ *   logits[r, v] = sum_k hidden[r, k] * W[v, k]
+ *   hidden [M, H] bf16, W [V, H] bf16 (one vocabulary entry per row),
+ *   logits [M, V] fp32.  bf16 MFMA, fp32 accumulation.  H % 64 == 0 required
+ *   (SPEC_ESHAPE otherwise); M and V are arbitrary (ragged tiles are handled).
+ * ------------------------------------------------------------------------- */
+int spec_lm_head(const void* hidden, const void* W, float* logits, int M, int H, int V, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * spec_accept — accepted length and bonus token per request (Method,
+ * "Rollback-Based Mode Selection": after the verification pass the target
+ * performs rejection sampling and identifies the rollback set).
+ *
+ * temperature[i] == 0: greedy.  g_j = argmax_v logits[row j] (lowest index on
+ *   ties); drafts are accepted while tokens[row j] == g_{j-1}; bonus = g_a.
+ * temperature[i]  > 0: rejection sampling with p_j = softmax(logits[row j]/T):
+ *   draft d_j = tokens[row j] (j >= 1) is accepted iff u_j * q_j(d_j) < p_{j-1}(d_j);
+ *   at the first rejection j* the bonus is drawn from norm(max(0, p_{j*-1} - q_{j*}));
+ *   if every draft is accepted it is drawn from p_gamma.  q_j is row
+ *   qo_indptr[i] - i + (j-1) of draft_probs; draft_probs == NULL means a
+ *   deterministic drafter (q_j one-hot at d_j).  Uniforms come from
+ *   Philox4x32-10 with key = seeds[i] (low, high word) and counter
+ *   (0, j, tag, round): tag 0 for the accept test of draft j, tag 1 for the
+ *   bonus draw at j* (or gamma_i + 1 when nothing is rejected); the first
+ *   output word's top 24 bits give u in [0, 1).  Probabilities, sums and
+ *   products are formed in fp64 and rounded to fp32 before they are compared.
+ *
+ *   logits [M, V] fp32; tokens [M] int32 (row 0 of a request = its last
+ *   committed token, unused here); draft_probs [M - B, V] fp32 or NULL;
+ *   temperature [B] fp32; seeds [B] uint64 (NULL allowed if all greedy).
+ * Outputs: accept_len [B] int32 (a_i in [0, gamma_i]); out_tokens
+ *   [B, gamma_max + 1] int32 = a_i accepted drafts, the bonus, then -1;
+ *   rollback [B] uint8 or NULL = (a_i < gamma_i); stats [4] int32 or NULL =
+ *   {number of rollback requests |R_n|, sum of emitted tokens, B, 0} for the
+ *   mode rule r_hat = |R_n| / B (eq. mode_switch_batch).
+ * A request with a bad row or token gets a_i = 0, bonus -1, and a flag.
+ * ------------------------------------------------------------------------- */
+size_t spec_accept_workspace_bytes(int B, int M, int V, int gamma_max);
+
+int spec_accept(const float* logits, const int32_t* tokens, const float* draft_probs,
+                const float* temperature, const uint64_t* seeds, uint32_t round,
+                const int32_t* qo_indptr,
+                int32_t* accept_len, int32_t* out_tokens, uint8_t* rollback, int32_t* stats,
+                int B, int M, int V, int gamma_max,
+                int32_t* status_flags,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * spec_kv_commit — Commit(p_n, y_n, L_n) on the KV cache (Appendix "Target
+ * side"; rollback frees the KV of the rejected suffix, Appendix "Draft side").
+ *   new_len_i = c_i + a_i + 1; pages ceil(new_len_i / P) .. ceil((c_i + n_i) / P) - 1
+ *   of request i are unmapped (-1) and appended to free_list in request order,
+ *   then logical-page order; seq_lens[i] <- new_len_i; *free_count grows.
+ *   accept_len values outside [0, gamma_i] are clamped.  No KV data moves: the
+ *   accepted tokens of a chain are a prefix of the candidate.
+ *   page_table [B, max_pages_per_seq] int32 in/out; seq_lens [B] in/out;
+ *   free_list [free_capacity] int32 in/out; free_count [1] int32 in/out.
+ *   If the list would overflow, the excess pages are still unmapped, are not
+ *   recorded, and SPEC_FLAG_FREE_OVERFLOW is raised.
+ * ------------------------------------------------------------------------- */
+int spec_kv_commit(int32_t* page_table, int max_pages_per_seq, int32_t* seq_lens,
+                   const int32_t* qo_indptr, const int32_t* accept_len,
+                   int32_t* free_list, int32_t free_capacity, int32_t* free_count,
+                   int B, int page_size, int32_t* status_flags, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEC_VERIFY_H */

@@ -1,0 +1,134 @@
+"""Thin Python binding of libspecverify.so: argument marshalling only.
+
+Every function has the name and the argument order of the C entry point in include/spec_verify.h and
+hands it device pointers of torch tensors plus torch's current HIP stream.  Nothing is computed here;
+if the library is missing the import fails (there is no fallback path).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspecverify.so")
+
+EXPORTS = (
+    "spec_last_error_string", "spec_version", "spec_set_tuning",
+    "spec_verify_attn_workspace_bytes", "spec_verify_attn", "spec_lm_head",
+    "spec_accept_workspace_bytes", "spec_accept", "spec_kv_commit",
+)
+
+FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
+
+
+class SpecError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"libspecverify status {code}: {text}")
+        self.code = code
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, f32, u32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_uint32, ctypes.c_size_t
+    lib.spec_last_error_string.restype = ctypes.c_char_p
+    lib.spec_last_error_string.argtypes = []
+    lib.spec_version.restype = i32
+    lib.spec_set_tuning.restype = i32
+    lib.spec_set_tuning.argtypes = [ctypes.c_char_p, i32]
+    lib.spec_verify_attn_workspace_bytes.restype = sz
+    lib.spec_verify_attn_workspace_bytes.argtypes = [i32] * 7
+    lib.spec_verify_attn.restype = i32
+    lib.spec_verify_attn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp,
+                                     i32, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, sz, vp]
+    lib.spec_lm_head.restype = i32
+    lib.spec_lm_head.argtypes = [vp, vp, vp, i32, i32, i32, vp]
+    lib.spec_accept_workspace_bytes.restype = sz
+    lib.spec_accept_workspace_bytes.argtypes = [i32] * 4
+    lib.spec_accept.restype = i32
+    lib.spec_accept.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.spec_kv_commit.restype = i32
+    lib.spec_kv_commit.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc):
+    if rc != 0:
+        raise SpecError(rc, _lib.spec_last_error_string().decode())
+
+
+def spec_version():
+    return _lib.spec_version()
+
+
+def spec_set_tuning(key: str, value: int):
+    _check(_lib.spec_set_tuning(key.encode(), int(value)))
+
+
+def spec_verify_attn_workspace_bytes(B, M, Hq, Hkv, D, max_kv_len, max_q_len):
+    return int(_lib.spec_verify_attn_workspace_bytes(B, M, Hq, Hkv, D, max_kv_len, max_q_len))
+
+
+def spec_verify_attn(q, k_cache, v_cache, page_table, seq_lens, qo_indptr, out, lse, max_kv_len, max_q_len, scale,
+                     status_flags, workspace):
+    M, Hq, D = q.shape
+    num_pages, Hkv, P, _ = k_cache.shape
+    B = seq_lens.shape[0]
+    _check(_lib.spec_verify_attn(
+        _ptr(q, torch.bfloat16), _ptr(k_cache, torch.bfloat16), _ptr(v_cache, torch.bfloat16),
+        _ptr(page_table, torch.int32), page_table.shape[1], num_pages, _ptr(seq_lens, torch.int32),
+        _ptr(qo_indptr, torch.int32), _ptr(out, torch.bfloat16), _ptr(lse, torch.float32),
+        B, M, Hq, Hkv, D, P, int(max_kv_len), int(max_q_len), float(scale), _ptr(status_flags, torch.int32),
+        _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
+
+
+def spec_lm_head(hidden, W, logits):
+    M, H = hidden.shape
+    V = W.shape[0]
+    assert W.shape[1] == H and tuple(logits.shape) == (M, V)
+    _check(_lib.spec_lm_head(_ptr(hidden, torch.bfloat16), _ptr(W, torch.bfloat16), _ptr(logits, torch.float32),
+                             M, H, V, _stream()))
+
+
+def spec_accept_workspace_bytes(B, M, V, gamma_max):
+    return int(_lib.spec_accept_workspace_bytes(B, M, V, gamma_max))
+
+
+def spec_accept(logits, tokens, draft_probs, temperature, seeds, round_, qo_indptr, accept_len, out_tokens, rollback,
+                stats, gamma_max, status_flags, workspace):
+    M, V = logits.shape
+    B = qo_indptr.shape[0] - 1
+    assert tuple(out_tokens.shape) == (B, gamma_max + 1)
+    _check(_lib.spec_accept(
+        _ptr(logits, torch.float32), _ptr(tokens, torch.int32), _ptr(draft_probs, torch.float32),
+        _ptr(temperature, torch.float32), _ptr(seeds, torch.int64), int(round_), _ptr(qo_indptr, torch.int32),
+        _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), _ptr(rollback, torch.uint8),
+        _ptr(stats, torch.int32), B, M, V, int(gamma_max), _ptr(status_flags, torch.int32),
+        _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
+
+
+def spec_kv_commit(page_table, seq_lens, qo_indptr, accept_len, free_list, free_count, page_size, status_flags):
+    B = seq_lens.shape[0]
+    _check(_lib.spec_kv_commit(
+        _ptr(page_table, torch.int32), page_table.shape[1], _ptr(seq_lens, torch.int32), _ptr(qo_indptr, torch.int32),
+        _ptr(accept_len, torch.int32), _ptr(free_list, torch.int32), free_list.shape[0], _ptr(free_count, torch.int32),
+        B, int(page_size), _ptr(status_flags, torch.int32), _stream()))

@@ -1,0 +1,472 @@
+// spec_accept: accepted length and bonus token per request (paper, Method, "Rollback-Based Mode
+// Selection": after the verification pass the target performs rejection sampling and identifies the
+// rollback set; Appendix "Target side": the target computes the accepted length L).
+//
+// Four kernels, all HBM-bound scans or tiny per-request work:
+//   1. row_stats      grid (segments, rows): per 4096-logit segment the max, the lowest argmax, a NaN
+//                     flag and, for sampled requests, sum exp((l - max_seg)/T) in fp64.
+//   2. decide         one wave per request: merges the segments of each row, then lane 0 walks the
+//                     drafts (prefix match, or u*q < p with a Philox uniform) and emits the accepted
+//                     drafts; greedy requests are finished here.
+//   3. residual_sums  grid (segments, requests): for sampled requests, fp64 segment sums of the
+//                     residual max(0, p - q) (and of p) on the one row the bonus is drawn from.
+//   4. pick           one workgroup per request: inverse CDF over segment sums, then inside the segment.
+// Probabilities are formed in fp64 and rounded to fp32 before they are compared or subtracted, so the
+// integer outputs do not depend on summation order beyond ~1e-16 relative.
+#include "common.h"
+
+namespace specv {
+
+constexpr int kSeg = 4096;          // logits per segment
+constexpr int kThreads = 256;
+constexpr int kPerThread = kSeg / kThreads;   // 16
+constexpr int kMaxRows = 64;        // gamma_max + 1 <= 64
+
+struct AcceptWorkspace {
+    float* seg_max;      // [M, nseg]
+    int32_t* seg_arg;    // [M, nseg]
+    int32_t* seg_bad;    // [M, nseg]
+    double* seg_z;       // [M, nseg]
+    double* res_sum;     // [B, nseg]
+    double* p_sum;       // [B, nseg]
+    double* job_m;       // [B]
+    double* job_z;       // [B]
+    float* job_u;        // [B]
+    float* job_t;        // [B]
+    int32_t* job_row;    // [B]  logits row the bonus is drawn from, -1 = nothing to draw
+    int32_t* job_qrow;   // [B]  draft_probs row subtracted, -1 = none
+    int32_t* job_onehot; // [B]  token of a one-hot drafter, -1 = none
+};
+
+static size_t carve(AcceptWorkspace* w, char* base, int B, int M, int nseg)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += round_up(bytes, 256); return p; };
+    const size_t rs = (size_t)M * nseg, bs = (size_t)B * nseg;
+    w->seg_z = (double*)take(rs * 8);
+    w->res_sum = (double*)take(bs * 8);
+    w->p_sum = (double*)take(bs * 8);
+    w->job_m = (double*)take((size_t)B * 8);
+    w->job_z = (double*)take((size_t)B * 8);
+    w->seg_max = (float*)take(rs * 4);
+    w->seg_arg = (int32_t*)take(rs * 4);
+    w->seg_bad = (int32_t*)take(rs * 4);
+    w->job_u = (float*)take((size_t)B * 4);
+    w->job_t = (float*)take((size_t)B * 4);
+    w->job_row = (int32_t*)take((size_t)B * 4);
+    w->job_qrow = (int32_t*)take((size_t)B * 4);
+    w->job_onehot = (int32_t*)take((size_t)B * 4);
+    return off;
+}
+
+// ---- Philox4x32-10 (Salmon et al., SC'11), written for the device ----------------------------
+__device__ inline float philox_uniform(uint64_t seed, uint32_t round, uint32_t j, uint32_t tag)
+{
+    uint32_t x0 = 0u, x1 = j, x2 = tag, x3 = round;
+    uint32_t ka = (uint32_t)seed, kb = (uint32_t)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, x0), lo0 = 0xD2511F53u * x0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, x2), lo1 = 0xCD9E8D57u * x2;
+        const uint32_t y0 = hi1 ^ x1 ^ ka, y2 = hi0 ^ x3 ^ kb;
+        x0 = y0; x1 = lo1; x2 = y2; x3 = lo0;
+        ka += 0x9E3779B9u;
+        kb += 0xBB67AE85u;
+    }
+    return (float)(x0 >> 8) * (1.0f / 16777216.0f);
+}
+
+// ---- reductions --------------------------------------------------------------------------------
+__device__ inline void wave_max_arg(float& m, int& a)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float om = __shfl_xor(m, d, 64);
+        const int oa = __shfl_xor(a, d, 64);
+        if (om > m || (om == m && oa < a)) { m = om; a = oa; }
+    }
+}
+
+__device__ inline double wave_sum(double x)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
+    return x;
+}
+
+__device__ inline int find_request(const int32_t* __restrict__ qo_indptr, int B, int row)
+{
+    int lo = 0, hi = B - 1;            // largest i with qo_indptr[i] <= row
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (qo_indptr[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// loads the 16 logits this thread owns in its segment; out-of-range slots read as -inf
+__device__ inline void load_strided(const float* __restrict__ row, int v0, int vend, bool vec, int tid, float (&x)[kPerThread])
+{
+#pragma unroll
+    for (int it = 0; it < kPerThread / 4; ++it) {
+        const int idx = v0 + (it * kThreads + tid) * 4;
+        if (vec && idx + 3 < vend) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(row + idx);
+            x[it * 4 + 0] = t.x; x[it * 4 + 1] = t.y; x[it * 4 + 2] = t.z; x[it * 4 + 3] = t.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) x[it * 4 + k] = (idx + k < vend) ? row[idx + k] : -INFINITY;
+        }
+    }
+}
+
+// ---- 1. per-segment statistics ---------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
+    const float* __restrict__ logits, const float* __restrict__ temperature,
+    const int32_t* __restrict__ qo_indptr, int B, int V, int nseg, bool vec,
+    AcceptWorkspace w, int32_t* __restrict__ stats)
+{
+    __shared__ float s_m[kThreads / 64];
+    __shared__ int s_a[kThreads / 64];
+    __shared__ int s_bad[kThreads / 64];
+    __shared__ double s_z[kThreads / 64];
+    const int seg = blockIdx.x, row = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (stats && seg == 0 && row == 0 && tid < 4) stats[tid] = (tid == 2) ? B : 0;
+    const float* lrow = logits + (size_t)row * V;
+    const int v0 = seg * kSeg, vend = min(V, v0 + kSeg);
+    float x[kPerThread];
+    load_strided(lrow, v0, vend, vec, tid, x);
+
+    float m = -INFINITY;
+    int arg = 0x7FFFFFFF, bad = 0;
+#pragma unroll
+    for (int it = 0; it < kPerThread / 4; ++it)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float xv = x[it * 4 + k];
+            bad |= (xv != xv);
+            if (xv > m) { m = xv; arg = v0 + (it * kThreads + tid) * 4 + k; }
+        }
+    wave_max_arg(m, arg);
+    bad = __any(bad);
+    if (lane == 0) { s_m[wave] = m; s_a[wave] = arg; s_bad[wave] = bad; }
+    __syncthreads();
+    float bm = s_m[0];
+    int ba = s_a[0], bb = s_bad[0];
+#pragma unroll
+    for (int k = 1; k < kThreads / 64; ++k) {
+        if (s_m[k] > bm || (s_m[k] == bm && s_a[k] < ba)) { bm = s_m[k]; ba = s_a[k]; }
+        bb |= s_bad[k];
+    }
+    const float T = temperature[find_request(qo_indptr, B, row)];
+    double z = 0.0;
+    if (T > 0.0f && !bb && bm > -INFINITY && bm < INFINITY) {
+        const double inv_t = 1.0 / (double)T, dm = (double)bm;
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) z += exp(((double)x[k] - dm) * inv_t);
+        z = wave_sum(z);
+        if (lane == 0) s_z[wave] = z;
+        __syncthreads();
+        z = 0.0;
+#pragma unroll
+        for (int k = 0; k < kThreads / 64; ++k) z += s_z[k];
+    }
+    if (tid == 0) {
+        const size_t o = (size_t)row * nseg + seg;
+        w.seg_max[o] = bm; w.seg_arg[o] = ba; w.seg_bad[o] = bb; w.seg_z[o] = z;
+    }
+}
+
+// ---- 2. per-request decision -----------------------------------------------------------------
+__global__ __launch_bounds__(64) void accept_decide_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ tokens, const float* __restrict__ draft_probs,
+    const float* __restrict__ temperature, const uint64_t* __restrict__ seeds, uint32_t round,
+    const int32_t* __restrict__ qo_indptr, int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens,
+    uint8_t* __restrict__ rollback, int32_t* __restrict__ stats, int V, int nseg, int gamma_max,
+    AcceptWorkspace w, int32_t* __restrict__ status_flags)
+{
+    __shared__ double s_m[kMaxRows], s_z[kMaxRows];
+    __shared__ int s_arg[kMaxRows], s_bad[kMaxRows];
+    const int i = blockIdx.x, lane = threadIdx.x;
+    const int r0 = qo_indptr[i], gamma = qo_indptr[i + 1] - r0 - 1;
+    int32_t* emit = out_tokens + (size_t)i * (gamma_max + 1);
+    for (int j = lane; j <= gamma_max; j += 64) emit[j] = -1;
+    if (lane == 0) { w.job_row[i] = -1; accept_len[i] = 0; if (rollback) rollback[i] = 0; }
+    if (gamma < 0 || gamma > gamma_max) {
+        if (lane == 0 && status_flags) atomicOr(status_flags, SPEC_FLAG_BAD_LENGTH);
+        return;
+    }
+    const float T = temperature[i];
+    const double Td = (double)T;
+    for (int j = 0; j <= gamma; ++j) {
+        const size_t base = (size_t)(r0 + j) * nseg;
+        float m = -INFINITY;
+        int arg = 0x7FFFFFFF, bad = 0;
+        for (int s = lane; s < nseg; s += 64) {
+            const float sm = w.seg_max[base + s];
+            const int sa = w.seg_arg[base + s];
+            bad |= w.seg_bad[base + s];
+            if (sm > m || (sm == m && sa < arg)) { m = sm; arg = sa; }
+        }
+        wave_max_arg(m, arg);
+        bad = __any(bad) || !(m > -INFINITY && m < INFINITY);
+        double z = 0.0;
+        if (T > 0.0f && !bad) {
+            for (int s = lane; s < nseg; s += 64) {
+                const float sm = w.seg_max[base + s];
+                if (sm > -INFINITY) z += w.seg_z[base + s] * exp(((double)sm - (double)m) / Td);
+            }
+            z = wave_sum(z);
+        }
+        if (lane == 0) { s_m[j] = (double)m; s_z[j] = z; s_arg[j] = arg; s_bad[j] = bad; }
+    }
+    __syncthreads();
+    if (lane != 0) return;
+
+    int flags = 0;
+    bool valid = (T >= 0.0f);
+    if (T > 0.0f && seeds == nullptr) { valid = false; flags |= SPEC_FLAG_NO_SEED; }
+    for (int j = 0; j <= gamma; ++j) if (s_bad[j]) { valid = false; flags |= SPEC_FLAG_BAD_LOGITS; }
+    for (int j = 1; j <= gamma; ++j) {
+        const int d = tokens[r0 + j];
+        if (d < 0 || d >= V) { valid = false; flags |= SPEC_FLAG_BAD_TOKEN; }
+    }
+    if (!(T >= 0.0f)) flags |= SPEC_FLAG_BAD_LOGITS;
+    int a = 0;
+    if (!valid) {
+        if (rollback) rollback[i] = (uint8_t)(gamma > 0);
+        if (stats) { if (gamma > 0) atomicAdd(stats + 0, 1); }
+        if (status_flags && flags) atomicOr(status_flags, flags);
+        return;
+    }
+    if (T == 0.0f) {
+        while (a < gamma && tokens[r0 + a + 1] == s_arg[a]) ++a;
+        emit[a] = s_arg[a];
+    } else {
+        const uint64_t seed = seeds[i];
+        int rejected_at = 0;
+        for (int j = 1; j <= gamma; ++j) {
+            const int d = tokens[r0 + j];
+            const double l = (double)logits[(size_t)(r0 + j - 1) * V + d];
+            const float p = (float)(exp((l - s_m[j - 1]) / Td) / s_z[j - 1]);
+            const float qd = draft_probs ? draft_probs[(size_t)(r0 - i + j - 1) * V + d] : 1.0f;
+            const float u = philox_uniform(seed, round, (uint32_t)j, 0u);
+            if ((float)((double)u * (double)qd) < p) ++a;
+            else { rejected_at = j; break; }
+        }
+        if (rejected_at) {
+            w.job_row[i] = r0 + rejected_at - 1;
+            w.job_qrow[i] = draft_probs ? (r0 - i + rejected_at - 1) : -1;
+            w.job_onehot[i] = draft_probs ? -1 : tokens[r0 + rejected_at];
+            w.job_u[i] = philox_uniform(seed, round, (uint32_t)rejected_at, 1u);
+            w.job_m[i] = s_m[rejected_at - 1];
+            w.job_z[i] = s_z[rejected_at - 1];
+        } else {
+            w.job_row[i] = r0 + gamma;
+            w.job_qrow[i] = -1;
+            w.job_onehot[i] = -1;
+            w.job_u[i] = philox_uniform(seed, round, (uint32_t)(gamma + 1), 1u);
+            w.job_m[i] = s_m[gamma];
+            w.job_z[i] = s_z[gamma];
+        }
+        w.job_t[i] = T;
+    }
+    for (int j = 0; j < a; ++j) emit[j] = tokens[r0 + j + 1];
+    accept_len[i] = a;
+    if (rollback) rollback[i] = (uint8_t)(a < gamma);
+    if (stats) {
+        if (a < gamma) atomicAdd(stats + 0, 1);
+        atomicAdd(stats + 1, a + 1);
+    }
+}
+
+// residual weight of vocabulary entry v on the job's row: max(0, p(v) - q(v)) in fp32, and p(v)
+__device__ inline void residual_of(float l, float qv, double m, double inv_t, double z, float& p, float& rho)
+{
+    p = (float)(exp(((double)l - m) * inv_t) / z);
+    const float diff = p - qv;
+    rho = diff > 0.0f ? diff : 0.0f;
+}
+
+// ---- 3. segment sums of the residual ---------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void accept_residual_sums_kernel(
+    const float* __restrict__ logits, const float* __restrict__ draft_probs, int V, int nseg, bool vec,
+    AcceptWorkspace w)
+{
+    __shared__ double s_r[kThreads / 64], s_p[kThreads / 64];
+    const int seg = blockIdx.x, i = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = w.job_row[i];
+    if (row < 0) return;
+    const int qrow = w.job_qrow[i], onehot = w.job_onehot[i];
+    const double m = w.job_m[i], z = w.job_z[i], inv_t = 1.0 / (double)w.job_t[i];
+    const int v0 = seg * kSeg, vend = min(V, v0 + kSeg);
+    float x[kPerThread], qv[kPerThread];
+    load_strided(logits + (size_t)row * V, v0, vend, vec, tid, x);
+    if (qrow >= 0) {
+        load_strided(draft_probs + (size_t)qrow * V, v0, vend, vec, tid, qv);
+    }
+    double rs = 0.0, ps = 0.0;
+#pragma unroll
+    for (int it = 0; it < kPerThread / 4; ++it)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int v = v0 + (it * kThreads + tid) * 4 + k;
+            if (v < vend) {
+                const float q = qrow >= 0 ? qv[it * 4 + k] : (v == onehot ? 1.0f : 0.0f);
+                float p, rho;
+                residual_of(x[it * 4 + k], q, m, inv_t, z, p, rho);
+                rs += (double)rho;
+                ps += (double)p;
+            }
+        }
+    rs = wave_sum(rs);
+    ps = wave_sum(ps);
+    if (lane == 0) { s_r[wave] = rs; s_p[wave] = ps; }
+    __syncthreads();
+    if (tid == 0) {
+        double r = 0.0, p = 0.0;
+        for (int k = 0; k < kThreads / 64; ++k) { r += s_r[k]; p += s_p[k]; }
+        w.res_sum[(size_t)i * nseg + seg] = r;
+        w.p_sum[(size_t)i * nseg + seg] = p;
+    }
+}
+
+// ---- 4. inverse CDF ----------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void accept_pick_kernel(
+    const float* __restrict__ logits, const float* __restrict__ draft_probs, const int32_t* __restrict__ accept_len,
+    int32_t* __restrict__ out_tokens, int V, int nseg, int gamma_max, AcceptWorkspace w)
+{
+    __shared__ int s_seg, s_use_p, s_best, s_last;
+    __shared__ double s_before, s_target, s_wave[kThreads / 64];
+    const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = w.job_row[i];
+    if (row < 0) return;
+    if (tid == 0) {
+        const double* rs = w.res_sum + (size_t)i * nseg;
+        double total = 0.0;
+        for (int s = 0; s < nseg; ++s) total += rs[s];
+        int use_p = 0;
+        if (!(total > 0.0)) {                  // p == q numerically: draw from p itself
+            use_p = 1;
+            rs = w.p_sum + (size_t)i * nseg;
+            total = 0.0;
+            for (int s = 0; s < nseg; ++s) total += rs[s];
+        }
+        const double target = (double)w.job_u[i] * total;
+        double run = 0.0;
+        int found = -1, last_pos = 0;
+        for (int s = 0; s < nseg; ++s) {
+            if (rs[s] > 0.0) last_pos = s;
+            if (run + rs[s] > target) { found = s; break; }
+            run += rs[s];
+        }
+        if (found < 0) {                       // rounding ran the CDF out: last segment with weight
+            found = last_pos;
+            run = 0.0;
+            for (int s = 0; s < found; ++s) run += rs[s];
+        }
+        s_seg = found; s_use_p = use_p; s_before = run; s_target = target;
+        s_best = 0x7FFFFFFF; s_last = -1;
+    }
+    __syncthreads();
+    const int seg = s_seg, use_p = s_use_p;
+    const int qrow = use_p ? -1 : w.job_qrow[i], onehot = use_p ? -1 : w.job_onehot[i];
+    const double m = w.job_m[i], z = w.job_z[i], inv_t = 1.0 / (double)w.job_t[i];
+    const int v0 = seg * kSeg + tid * kPerThread;          // this thread owns 16 consecutive entries
+    const float* lrow = logits + (size_t)row * V;
+    const float* qptr = qrow >= 0 ? draft_probs + (size_t)qrow * V : nullptr;
+    float rho[kPerThread];
+    double mine = 0.0;
+    int my_last = -1;
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        const int v = v0 + k;
+        rho[k] = 0.0f;
+        if (v < V) {
+            const float q = qptr ? qptr[v] : (v == onehot ? 1.0f : 0.0f);
+            float p, r;
+            residual_of(lrow[v], q, m, inv_t, z, p, r);
+            rho[k] = use_p ? p : r;
+            if (rho[k] > 0.0f) my_last = v;
+        }
+        mine += (double)rho[k];
+    }
+    // exclusive prefix of the per-thread sums, in thread order
+    double incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const double up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+    }
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    double before = s_before;
+    for (int k = 0; k < wave; ++k) before += s_wave[k];
+    double run = before + (incl - mine);
+    const double target = s_target;
+    int hit = 0x7FFFFFFF;
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+        run += (double)rho[k];
+        if (hit == 0x7FFFFFFF && run > target && v0 + k < V) hit = v0 + k;
+    }
+    if (hit != 0x7FFFFFFF) atomicMin(&s_best, hit);
+    if (my_last >= 0) atomicMax(&s_last, my_last);
+    __syncthreads();
+    if (tid == 0) {
+        const int bonus = s_best != 0x7FFFFFFF ? s_best : s_last;
+        out_tokens[(size_t)i * (gamma_max + 1) + accept_len[i]] = bonus;
+    }
+}
+
+}  // namespace specv
+
+static int accept_nseg(int V) { return (V + specv::kSeg - 1) / specv::kSeg; }
+
+extern "C" size_t spec_accept_workspace_bytes(int B, int M, int V, int gamma_max)
+{
+    (void)gamma_max;
+    if (B < 0 || M < 0 || V <= 0) return 0;
+    specv::AcceptWorkspace w;
+    return specv::carve(&w, nullptr, B, M, accept_nseg(V));
+}
+
+extern "C" int spec_accept(const float* logits, const int32_t* tokens, const float* draft_probs,
+                           const float* temperature, const uint64_t* seeds, uint32_t round,
+                           const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
+                           uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                           int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace specv;
+    if (B < 0 || M < 0 || V <= 0 || gamma_max < 0)
+        return fail(SPEC_EINVAL, "spec_accept: negative size (B=%d M=%d V=%d gamma_max=%d)", B, M, V, gamma_max);
+    if (B == 0) return SPEC_OK;
+    if (!logits || !tokens || !temperature || !qo_indptr || !accept_len || !out_tokens)
+        return fail(SPEC_EINVAL, "spec_accept: NULL pointer argument");
+    if (gamma_max + 1 > kMaxRows)
+        return fail(SPEC_ESHAPE, "spec_accept: gamma_max=%d, at most %d candidate rows per request", gamma_max, kMaxRows);
+    if (M < B) return fail(SPEC_EINVAL, "spec_accept: M=%d < B=%d (every request has at least one row)", M, B);
+    const int nseg = accept_nseg(V);
+    if (nseg > 65535 || M > 65535 || B > 65535)
+        return fail(SPEC_ESHAPE, "spec_accept: V=%d or M=%d beyond the launch grid", V, M);
+    AcceptWorkspace w;
+    const size_t need = carve(&w, nullptr, B, M, nseg);
+    if (!workspace || !aligned(workspace, 256))
+        return fail(SPEC_EINVAL, "spec_accept: workspace is NULL or not 256-byte aligned");
+    if (workspace_bytes < need)
+        return fail(SPEC_EWORKSPACE, "spec_accept: workspace %zu bytes, need %zu", workspace_bytes, need);
+    carve(&w, (char*)workspace, B, M, nseg);
+    const bool vec = (V % 4 == 0) && aligned(logits, 16) && (!draft_probs || aligned(draft_probs, 16));
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(accept_row_stats_kernel, dim3(nseg, M), dim3(kThreads), 0, s, logits, temperature, qo_indptr, B,
+                       V, nseg, vec, w, stats);
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(64), 0, s, logits, tokens, draft_probs, temperature, seeds,
+                       round, qo_indptr, accept_len, out_tokens, rollback, stats, V, nseg, gamma_max, w, status_flags);
+    if (seeds) {   // seeds == NULL promises an all-greedy batch: nothing is ever drawn
+        hipLaunchKernelGGL(accept_residual_sums_kernel, dim3(nseg, B), dim3(kThreads), 0, s, logits, draft_probs, V,
+                           nseg, vec, w);
+        hipLaunchKernelGGL(accept_pick_kernel, dim3(B), dim3(kThreads), 0, s, logits, draft_probs, accept_len,
+                           out_tokens, V, nseg, gamma_max, w);
+    }
+    return check_launch("spec_accept");
+}

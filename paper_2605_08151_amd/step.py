@@ -1,0 +1,46 @@
+"""One verification step = the four library calls in order, with their scratch buffers.
+
+Glue for tests and the benchmark: owns torch-allocated workspaces and outputs, nothing numerical.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as sv
+
+
+class VerifyStep:
+    def __init__(self, B, M, Hq, Hkv, D, H, V, gamma_max, max_kv_len, device="cuda"):
+        self.B, self.M, self.Hq, self.Hkv, self.D, self.H, self.V = B, M, Hq, Hkv, D, H, V
+        self.gamma_max, self.max_kv_len = gamma_max, max_kv_len
+        dev = torch.device(device)
+        self.attn_ws = torch.empty(max(256, sv.spec_verify_attn_workspace_bytes(B, M, Hq, Hkv, D, max_kv_len, gamma_max + 1)),
+                                   dtype=torch.uint8, device=dev)
+        self.accept_ws = torch.empty(max(256, sv.spec_accept_workspace_bytes(B, M, V, gamma_max)), dtype=torch.uint8, device=dev)
+        self.attn_out = torch.empty((M, Hq, D), dtype=torch.bfloat16, device=dev)
+        self.lse = torch.empty((M, Hq), dtype=torch.float32, device=dev)
+        self.logits = torch.empty((M, V), dtype=torch.float32, device=dev)
+        self.accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+        self.out_tokens = torch.empty((B, gamma_max + 1), dtype=torch.int32, device=dev)
+        self.rollback = torch.empty(B, dtype=torch.uint8, device=dev)
+        self.stats = torch.zeros(4, dtype=torch.int32, device=dev)
+        self.status = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def attn(self, q, k_cache, v_cache, page_table, seq_lens, qo_indptr, scale, want_lse=True):
+        sv.spec_verify_attn(q, k_cache, v_cache, page_table, seq_lens, qo_indptr, self.attn_out,
+                            self.lse if want_lse else None, self.max_kv_len, self.gamma_max + 1, scale, self.status,
+                            self.attn_ws)
+        return self.attn_out
+
+    def lm_head(self, hidden, W):
+        sv.spec_lm_head(hidden, W, self.logits)
+        return self.logits
+
+    def accept(self, tokens, draft_probs, temperature, seeds, round_, qo_indptr, logits=None):
+        sv.spec_accept(self.logits if logits is None else logits, tokens, draft_probs, temperature, seeds, round_,
+                       qo_indptr, self.accept_len, self.out_tokens, self.rollback, self.stats, self.gamma_max,
+                       self.status, self.accept_ws)
+        return self.accept_len, self.out_tokens
+
+    def commit(self, page_table, seq_lens, qo_indptr, free_list, free_count, page_size=16):
+        sv.spec_kv_commit(page_table, seq_lens, qo_indptr, self.accept_len, free_list, free_count, page_size, self.status)
