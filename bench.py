@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the verification step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mid]
+
+A step is one pass of the whole hot path over one synthetic batch, inputs resident in HBM:
+spec_verify_attn -> spec_lm_head -> spec_accept -> spec_kv_commit.  Prints ONE JSON line: verified
+tokens/s (sum of accepted drafts + bonus tokens per wall-clock second), the roofline figures of the
+dominant kernel measured with HIP events on the launch stream, per-call timings, and the CPU oracle
+timed on a bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="mid", help="workload name in paper_2605_08151_amd.workloads.CONFIGS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attn-chunk", type=int, default=0, help="override keys per kv split (0 = library heuristic)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives are implemented); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2605_08151_amd import binding as sv
+    from paper_2605_08151_amd import workloads as wl
+    from paper_2605_08151_amd.step import VerifyStep
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.config]
+    if args.attn_chunk:
+        sv.spec_set_tuning("attn_chunk", args.attn_chunk)
+
+    # ---- inputs (untimed) ------------------------------------------------------------------
+    kv_copies = 2
+    b = wl.make_batch(cfg, device="cuda", kv_copies=kv_copies)
+    B, M, V, H = b["B"], b["M"], cfg.V, cfg.H
+    step = VerifyStep(B, M, cfg.Hq, cfg.Hkv, cfg.D, H, V, b["gamma_max"], b["max_kv_len"])
+    qo = b["qo_indptr"]
+    logits = step.lm_head(b["hidden"], b["W"])
+    torch.cuda.synchronize()
+    stochastic = bool((b["temperature"] > 0).any())
+    tokens_g, _ = wl.draft_tokens_greedy(cfg, qo, logits.argmax(1).cpu())
+    draft_probs, tokens = None, tokens_g
+    if stochastic:
+        draft_probs, tokens_s = wl.draft_probs_noisy(cfg, qo, logits)
+        per_row_T = torch.repeat_interleave(b["temperature"].cpu(), (qo[1:] - qo[:-1]).cpu().long())
+        tokens = torch.where(per_row_T > 0, tokens_s, tokens_g)
+    tokens = tokens.cuda()
+    seeds = b["seeds"] if stochastic else None
+
+    # commit mutates the page table / lengths / free list: give every step its own pristine copy
+    total = args.steps + args.warmup
+    states = [(b["page_table"].clone(), b["seq_lens"].clone(), b["free_list"].clone(), b["free_count"].clone())
+              for _ in range(total)]
+
+    names = ("verify_attn", "lm_head", "accept", "kv_commit")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+
+    def run(k, events=None):
+        pt, sl, fl, fc = states[k]
+        kc, vc = b["k_caches"][k % kv_copies], b["v_caches"][k % kv_copies]
+        if events: events[0].record()
+        step.attn(b["q"], kc, vc, pt, sl, qo, b["scale"], want_lse=False)
+        if events: events[1].record()
+        step.lm_head(b["hidden"], b["W"])
+        if events: events[2].record()
+        step.accept(tokens, draft_probs, b["temperature"], seeds, 0, qo)
+        if events: events[3].record()
+        step.commit(pt, sl, qo, fl, fc, cfg.P)
+        if events: events[4].record()
+
+    for k in range(args.warmup):
+        run(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        run(args.warmup + k, ev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    emitted = int(step.stats.cpu()[1])
+    assert int(step.status.cpu()) == 0, "a kernel flagged bad input"
+    per_call_ms = {n: float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)]))
+                   for i, n in enumerate(names)}
+
+    # ---- roofline of each call (algorithmic bytes / flops per launch) -----------------------
+    kv_tokens = int((b["ctx"] + b["gammas"] + 1).sum())
+    attn_bytes = kv_tokens * cfg.Hkv * cfg.D * 2 * 2 + 2 * M * cfg.Hq * cfg.D * 2
+    lm_bytes = V * H * 2 + M * H * 2 + M * V * 4
+    lm_flops = 2.0 * M * H * V
+    n_stoch = int((b["temperature"] > 0).sum())
+    accept_bytes = M * V * 4 + n_stoch * 2 * V * 4
+    rl = {
+        "verify_attn": dict(bound="hbm", achieved=attn_bytes / per_call_ms["verify_attn"] / 1e6, peak=HBM_PEAK_GBS, unit="GB/s"),
+        "lm_head_hbm": dict(bound="hbm", achieved=lm_bytes / per_call_ms["lm_head"] / 1e6, peak=HBM_PEAK_GBS, unit="GB/s"),
+        "lm_head_mfma": dict(bound="mfma", achieved=lm_flops / per_call_ms["lm_head"] / 1e9, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s"),
+        "accept": dict(bound="hbm", achieved=accept_bytes / per_call_ms["accept"] / 1e6, peak=HBM_PEAK_GBS, unit="GB/s"),
+    }
+    for r in rl.values():
+        r["frac"] = r["achieved"] / r["peak"]
+    dominant = max(names, key=lambda n: per_call_ms[n])
+    # the LM head is priced against the roof that binds it at this M: weight streaming (HBM) when the
+    # arithmetic intensity is under the ridge, MFMA otherwise
+    lm_key = "lm_head_hbm" if lm_flops / lm_bytes < MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS else "lm_head_mfma"
+    dom_key = {"lm_head": lm_key, "kv_commit": "accept"}.get(dominant, dominant)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"{cfg.name}:{dominant}")
+    roofline = dict(kernel=dominant, **rl[dom_key], traffic=traffic)
+
+    # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, b, step, tokens, draft_probs, seeds, emitted_per_step=emitted)
+
+    out = {
+        "metric": "verified tokens/sec per GPU", "value": emitted / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={B} gamma={sorted(set(b['gammas'].tolist()))} M={M} ctx={cfg.ctx} "
+                               f"Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} page={cfg.P} H={H} V={V} "
+                               f"temperature={cfg.temperature} seed={cfg.seed}",
+                   "emitted_tokens_per_step": emitted, "scored_positions_per_step": M,
+                   "scored_positions_per_s": M / (ms_per_step * 1e-3), "kv_tokens": kv_tokens},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "per_call_ms": per_call_ms,
+        "per_call_roofline": rl,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(cfg, b, step, tokens, draft_probs, seeds, emitted_per_step):
+    """Times the oracle on a slice of the batch sized for ~10-30 s and extrapolates linearly per stage."""
+    import numpy as np
+    import oracle
+    from paper_2605_08151_amd import workloads as wl
+
+    oracle.build()
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or os.cpu_count()
+    B, M, V = b["B"], b["M"], cfg.V
+    qo = b["qo_indptr"].cpu().numpy()
+    # attention: first n_seq requests (all heads, all rows)
+    n_seq = min(B, 4)
+    rows = int(qo[n_seq])
+    kbits, vbits = wl.bf16_bits(b["k_cache"]), wl.bf16_bits(b["v_cache"])
+    t = time.perf_counter()
+    oracle.verify_attn(wl.bf16_bits(b["q"][:rows]), kbits, vbits, b["page_table"][:n_seq].cpu().numpy(),
+                       b["ctx"][:n_seq].numpy().astype(np.int32), qo[:n_seq + 1].copy(), b["scale"])
+    t_attn_sample = time.perf_counter() - t
+    w_all = float(((b["ctx"] + b["gammas"] + 1) * (b["gammas"] + 1)).sum())
+    w_s = float(((b["ctx"][:n_seq] + b["gammas"][:n_seq] + 1) * (b["gammas"][:n_seq] + 1)).sum())
+    t_attn = t_attn_sample * w_all / w_s
+    # LM head: all rows against the first v_s vocabulary entries
+    v_s = min(V, max(256, int(6.0e10 / (2.0 * M * cfg.H))))
+    t = time.perf_counter()
+    oracle.lm_head(wl.bf16_bits(b["hidden"]), wl.bf16_bits(b["W"][:v_s]))
+    t_lm = (time.perf_counter() - t) * V / v_s
+    # acceptance and commit: whole batch, on the GPU's logits
+    gl = step.logits.cpu().numpy()
+    dp = None if draft_probs is None else draft_probs.cpu().numpy()
+    sd = None if seeds is None else seeds.cpu().numpy().view(np.uint64)
+    t = time.perf_counter()
+    ref = oracle.accept(gl, tokens.cpu().numpy(), dp, b["temperature"].cpu().numpy(), sd, 0, qo, b["gamma_max"])
+    t_acc = time.perf_counter() - t
+    pt, sl = b["page_table"].cpu().numpy().copy(), b["ctx"].numpy().astype(np.int32).copy()
+    fl, fc = b["free_list"].cpu().numpy().copy(), b["free_count"].cpu().numpy().copy()
+    t = time.perf_counter()
+    oracle.kv_commit(pt, sl, qo, ref["accept_len"], fl, fc, cfg.P)
+    t_commit = time.perf_counter() - t
+    total = t_attn + t_lm + t_acc + t_commit
+    return {"value": emitted_per_step / total, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"attention on the first {n_seq} of {B} requests ({t_attn_sample:.2f} s, scaled by key*row count), "
+                      f"LM head on all {M} rows x first {v_s} of {V} vocabulary rows (scaled by V), "
+                      f"acceptance and commit on the whole batch; stage seconds at full size: "
+                      f"attn {t_attn:.2f}, lm_head {t_lm:.2f}, accept {t_acc:.3f}, commit {t_commit:.4f}"}
+
+
+if __name__ == "__main__":
+    main()

@@ -182,7 +182,7 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ tokens, const float* __restrict__ draft_probs,
     const float* __restrict__ temperature, const uint64_t* __restrict__ seeds, uint32_t round,
     const int32_t* __restrict__ qo_indptr, int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens,
-    uint8_t* __restrict__ rollback, int32_t* __restrict__ stats, int V, int nseg, int gamma_max,
+    uint8_t* __restrict__ rollback, int32_t* __restrict__ stats, int M, int V, int nseg, int gamma_max,
     AcceptWorkspace w, int32_t* __restrict__ status_flags)
 {
     __shared__ double s_m[kMaxRows], s_z[kMaxRows];
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
     int32_t* emit = out_tokens + (size_t)i * (gamma_max + 1);
     for (int j = lane; j <= gamma_max; j += 64) emit[j] = -1;
     if (lane == 0) { w.job_row[i] = -1; accept_len[i] = 0; if (rollback) rollback[i] = 0; }
-    if (gamma < 0 || gamma > gamma_max) {
+    if (gamma < 0 || gamma > gamma_max || r0 < 0 || r0 + gamma + 1 > M) {
         if (lane == 0 && status_flags) atomicOr(status_flags, SPEC_FLAG_BAD_LENGTH);
         return;
     }
@@ -461,7 +461,7 @@ extern "C" int spec_accept(const float* logits, const int32_t* tokens, const flo
     hipLaunchKernelGGL(accept_row_stats_kernel, dim3(nseg, M), dim3(kThreads), 0, s, logits, temperature, qo_indptr, B,
                        V, nseg, vec, w, stats);
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(64), 0, s, logits, tokens, draft_probs, temperature, seeds,
-                       round, qo_indptr, accept_len, out_tokens, rollback, stats, V, nseg, gamma_max, w, status_flags);
+                       round, qo_indptr, accept_len, out_tokens, rollback, stats, M, V, nseg, gamma_max, w, status_flags);
     if (seeds) {   // seeds == NULL promises an all-greedy batch: nothing is ever drawn
         hipLaunchKernelGGL(accept_residual_sums_kernel, dim3(nseg, B), dim3(kThreads), 0, s, logits, draft_probs, V,
                            nseg, vec, w);

@@ -40,13 +40,13 @@ struct AttnParams {
     float* part_m;      // [M*Hq, splits]   running max, log2 domain
     float* part_l;      // [M*Hq, splits]
     int32_t* status_flags;
-    int max_pages, num_pages, Hq, Hkv, G, max_kv_len, max_q_len, chunk_target, splits;
+    int max_pages, num_pages, Hq, Hkv, G, M, max_kv_len, max_q_len, chunk_target, splits;
     float scale_log2e;
 };
 
-__device__ inline bool request_ok(int n, int c, int max_q_len, int max_kv_len)
+__device__ inline bool request_ok(int r0, int n, int c, const AttnParams& p)
 {
-    return n >= 1 && n <= max_q_len && c >= 0 && c + n <= max_kv_len;
+    return n >= 1 && n <= p.max_q_len && r0 >= 0 && r0 + n <= p.M && c >= 0 && c + n <= p.max_kv_len;
 }
 
 template <int NR>
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
     const int split = blockIdx.x, kvh = blockIdx.y, i = blockIdx.z;
 
     const int r0 = p.qo_indptr[i], n = p.qo_indptr[i + 1] - r0, c = p.seq_lens[i];
-    if (!request_ok(n, c, p.max_q_len, p.max_kv_len)) {
+    if (!request_ok(r0, n, c, p)) {
         if (split == 0 && kvh == 0 && tid == 0 && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_LENGTH);
         return;
     }
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(128) void verify_attn_combine_kernel(AttnParams p, 
     }
     const int i = lo;
     const int n = p.qo_indptr[i + 1] - p.qo_indptr[i], c = p.seq_lens[i];
-    if (!request_ok(n, c, p.max_q_len, p.max_kv_len)) return;
+    if (!request_ok(p.qo_indptr[i], n, c, p) || row >= p.qo_indptr[i + 1]) return;
     const int len = c + n;
     const int ns = (len + p.chunk_target - 1) / p.chunk_target;
     const size_t unit = ((size_t)row * p.Hq + hq) * p.splits;
@@ -425,7 +425,7 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
     p.page_table = page_table; p.seq_lens = seq_lens; p.qo_indptr = qo_indptr;
     p.status_flags = status_flags;
     p.max_pages = max_pages_per_seq; p.num_pages = num_pages; p.Hq = Hq; p.Hkv = Hkv; p.G = G;
-    p.max_kv_len = max_kv_len; p.max_q_len = max_q_len;
+    p.M = M; p.max_kv_len = max_kv_len; p.max_q_len = max_q_len;
     p.chunk_target = attn_chunk_target(B, Hkv, max_kv_len);
     p.splits = (max_kv_len + p.chunk_target - 1) / p.chunk_target;
     p.scale_log2e = scale * 1.4426950408889634f;
