@@ -102,6 +102,202 @@ __global__ __launch_bounds__(256) void lm_head_tiled_kernel(
         }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Weight-streaming kernel for M <= 160 rows (the verify batches of BASELINE configs 1, 2 and 4):
+// the roof is HBM (W is read once, 2*V*H bytes), so the layout is built around the W stream.
+//   * One persistent workgroup per CU owns a contiguous range of vocabulary entries and walks it in
+//     passes of 4 waves x 32 entries; the last pass is split evenly over the waves so that all CUs
+//     finish together whatever V is.  Only 32 rows of W per wave are open at a time: measured on
+//     MI355X, a read stream over 8 KB-strided rows reaches ~5.7 TB/s with 128 rows in flight per CU
+//     but only ~4.7 TB/s with 256, against ~6.0 TB/s for a linear read.
+//   * Each wave reads ITS vocabulary rows straight from HBM into registers in MFMA operand order
+//     (v_mfma_f32_16x16x32_bf16, W on the A side: lane (entry l%16, k-group l/16) takes 16 B at
+//     k = 32c + 8*(l/16), so the four lanes of a row cover 64 contiguous bytes per instruction).
+//     The registers form a ring of 512 k: a chunk is re-requested 512 k ahead right after the MFMAs
+//     that consumed it.  No W byte touches LDS.
+//   * hidden (all M rows, L2-resident) is staged through LDS in 128-wide k slabs shared by the waves.
+//   * C^T tiles come out with 4 consecutive vocabulary entries per lane: 16-byte stores along V.
+// ------------------------------------------------------------------------------------------------
+constexpr int kSlab = 128;                   // k per hidden slab in LDS
+constexpr int kRingSlabs = 4;                // W register ring: 4 slabs = 16 chunks of 32 k = 512 k ahead
+constexpr int kRing = 4 * kRingSlabs;
+constexpr int kHPitch = kSlab * 2 + 16;      // bytes per hidden row in LDS (272: 16 rows -> 16 bank groups)
+constexpr int kPassCols = 128;               // vocabulary entries per workgroup pass (4 waves x 32)
+
+template <int TM, int TN>
+__device__ inline void skinny_pass(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
+                                   int M, int H, int V, int wave_c0, int wave_nc, bool vec_store,
+                                   unsigned char* smem, int tid)
+{
+    constexpr int BM = TM * 16;
+    constexpr int H_LOADS = BM * 16 / 256;            // 16-byte chunks of a hidden slab per thread (= TM)
+    const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+
+    f32x4 acc[TN][TM];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint16_t* wptr[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        // entries past the wave's range read a valid row instead (branch-free loop); their results are never stored
+        wptr[tn] = W + (size_t)min(wave_c0 + tn * 16 + l16, V - 1) * H + kg * 8;
+    }
+    // Loads retire in order, so waiting for a young hidden load would drain the whole W ring.  The
+    // hidden slab s+2 is therefore requested at the start of slab s and only stashed at the end of slab
+    // s+1, when every load older than it is one the math needed anyway.
+    u32x4 wreg[TN][kRing], hreg[2][H_LOADS];
+    auto fetch_w = [&](int c, int k0) {               // chunk c of the ring <- k0 + 32*(c%4) .. +32
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) wreg[tn][c] = *reinterpret_cast<const u32x4*>(wptr[tn] + k0 + (c & 3) * 32);
+    };
+    auto fetch_h = [&](int set, int k0) {
+#pragma unroll
+        for (int p = 0; p < H_LOADS; ++p) {
+            // rows past M read row M-1: every output row depends on its own hidden row only
+            const int idx = tid + p * 256, row = min(idx >> 4, M - 1), ch = idx & 15;
+            hreg[set][p] = *reinterpret_cast<const u32x4*>(A + (size_t)row * H + k0 + ch * 8);
+        }
+    };
+    auto stash_h = [&](int set, unsigned char* buf) {
+#pragma unroll
+        for (int p = 0; p < H_LOADS; ++p) {
+            const int idx = tid + p * 256, row = idx >> 4, ch = idx & 15;
+            *reinterpret_cast<u32x4*>(buf + row * kHPitch + ch * 16) = hreg[set][p];
+        }
+    };
+
+    const int nslab = H / kSlab;                       // multiple of kRingSlabs
+    unsigned char* buf0 = smem;
+    unsigned char* buf1 = smem + BM * kHPitch;
+    __syncthreads();                                  // previous pass is done with both buffers
+    // Prologue in the order of the steady state (hidden slab, then W chunks), so that the wait counts the
+    // compiler derives for the loop entry are not tighter than those of the back edge.
+    fetch_h(0, 0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) fetch_w(c, 0);
+    fetch_h(1, kSlab);                                // slab 1, stashed at the end of slab 0
+#pragma unroll
+    for (int c = 4; c < kRing; ++c) fetch_w(c, (c >> 2) * kSlab);
+    stash_h(0, buf0);
+    __syncthreads();
+    for (int s4 = 0; s4 < nslab; s4 += kRingSlabs) {
+#pragma unroll
+        for (int par = 0; par < kRingSlabs; ++par) {
+            const int s = s4 + par;
+            unsigned char* cur = (par & 1) ? buf1 : buf0;
+            unsigned char* nxt = (par & 1) ? buf0 : buf1;   // last read in slab s-1, before the barrier that ended it
+            // past the end the prefetches wrap to a valid slab (L2 hits, results unused): no branch in the loop
+            const int kh = min((s + 2) * kSlab, H - kSlab);
+            const int kw = min((s + kRingSlabs) * kSlab, H - kSlab);
+            fetch_h(par & 1, kh);
+            // The scheduler must not move the loads: their program order is what the in-order wait
+            // counters are derived from (see above), so every step is fenced.
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8 hf[2][TM];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                hf[0][tm] = *reinterpret_cast<const bf16x8*>(cur + (tm * 16 + l16) * kHPitch + kg * 16);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (c < 3) {
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+                        hf[(c + 1) & 1][tm] = *reinterpret_cast<const bf16x8*>(cur + (tm * 16 + l16) * kHPitch + (c + 1) * 64 + kg * 16);
+                }
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[tn][par * 4 + c]);
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, hf[c & 1][tm], acc[tn][tm], 0, 0, 0);
+                }
+                fetch_w(par * 4 + c, kw);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            stash_h((par & 1) ^ 1, nxt);              // slab s+1, requested one slab ago
+            __syncthreads();
+        }
+    }
+    // acc[tn][tm][i] = C[row 16tm + l16][entry wave_c0 + 16tn + 4kg + i]
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int e = tn * 16 + kg * 4;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int row = tm * 16 + l16;
+            if (row < M && e < wave_nc) {
+                float* dst = C + (size_t)row * V + wave_c0 + e;
+                if (vec_store && e + 3 < wave_nc) {
+                    *reinterpret_cast<f32x4*>(dst) = acc[tn][tm];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (e + i < wave_nc) dst[i] = acc[tn][tm][i];
+                }
+            }
+        }
+    }
+}
+
+template <int TM>
+__global__ __launch_bounds__(256, 1) void lm_head_skinny_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
+    int M, int H, int V, int cols_per_wg, bool vec_store)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c_begin = blockIdx.x * cols_per_wg;
+    const int c_end = min(V, c_begin + cols_per_wg);
+    for (int pass0 = c_begin; pass0 < c_end; pass0 += kPassCols) {
+        const int pass_cols = min(kPassCols, c_end - pass0);
+        const int per_wave = pass_cols == kPassCols ? kPassCols / 4 : (((pass_cols + 3) / 4 + 3) & ~3);
+        const int wave_c0 = pass0 + wave * per_wave;
+        int wave_nc = pass_cols - wave * per_wave;
+        wave_nc = wave_nc < 0 ? 0 : (wave_nc > per_wave ? per_wave : wave_nc);
+        if (per_wave > 16) skinny_pass<TM, 2>(A, W, C, M, H, V, wave_c0, wave_nc, vec_store, smem, tid);
+        else skinny_pass<TM, 1>(A, W, C, M, H, V, wave_c0, wave_nc, vec_store, smem, tid);
+    }
+}
+
+static int device_cu_count()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+template <int TM>
+static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
+{
+    const size_t smem = 2 * (size_t)TM * 16 * kHPitch;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
+        configured = true;
+    }
+    const int cus = device_cu_count();
+    int cols = ((V + cus - 1) / cus + 3) & ~3;
+    if (cols < 64) cols = 64;
+    const int grid = (V + cols - 1) / cols;
+    const bool vec_store = (V % 4 == 0);
+    hipLaunchKernelGGL(lm_head_skinny_kernel<TM>, dim3(grid), dim3(256), smem, s, a, w, c, M, H, V, cols, vec_store);
+    return SPEC_OK;
+}
+
 }  // namespace specv
 
 extern "C" int spec_lm_head(const void* hidden, const void* W, float* logits, int M, int H, int V, void* stream)
@@ -116,7 +312,15 @@ extern "C" int spec_lm_head(const void* hidden, const void* W, float* logits, in
     hipStream_t s = (hipStream_t)stream;
     const uint16_t* a = (const uint16_t*)hidden;
     const uint16_t* w = (const uint16_t*)W;
-    if (M <= 64) {
+    if (M <= 160 && H % (kRingSlabs * kSlab) == 0) {
+        int rc;
+        if (M <= 32) rc = launch_skinny<2>(a, w, logits, M, H, V, s);
+        else if (M <= 64) rc = launch_skinny<4>(a, w, logits, M, H, V, s);
+        else if (M <= 96) rc = launch_skinny<6>(a, w, logits, M, H, V, s);
+        else if (M <= 128) rc = launch_skinny<8>(a, w, logits, M, H, V, s);
+        else rc = launch_skinny<10>(a, w, logits, M, H, V, s);
+        if (rc != SPEC_OK) return rc;
+    } else if (M <= 64) {
         const long tiles = (long)((M + 63) / 64) * ((V + 127) / 128);
         hipLaunchKernelGGL((lm_head_tiled_kernel<64, 128>), dim3((unsigned)tiles), dim3(256), 0, s, a, w, logits, M, H, V);
     } else {
