@@ -4,13 +4,16 @@
 //
 // Work decomposition (HBM-bound: 512 bytes of K+V per key per kv head, 8..72 flop per byte):
 //   grid = (kv split, kv head, request).  A workgroup of 4 waves streams one contiguous chunk of one
-//   request's keys for one kv head in tiles of 128 keys (8 pages); wave w owns keys 32w..32w+31 of
-//   every tile and all G * n_i query rows (query heads of the group x candidate positions), so no
-//   K/V byte is read from LDS twice and waves only meet at the tile barriers.
+//   request's keys for one kv head; wave w owns keys 32w..32w+31 of every 128-key step and all
+//   G * n_i query rows (query heads of the group x candidate positions).  A wave copies ITS two pages
+//   (K and V, 4 KB each, contiguous in HBM) straight into its private 16 KB of LDS with direct
+//   global->LDS loads (no staging registers), so the waves of a workgroup never wait for each other
+//   inside the loop; latency is hidden by the other waves resident on the SIMD.
 //   Scores are computed transposed, S^T = K Q^T (v_mfma_f32_16x16x32_bf16, keys on the MFMA row
 //   axis): a lane then holds 4 keys of ONE query row, the row maximum is an in-lane max plus two
-//   cross-lane shuffles, and exp(S^T) is already the B operand of O^T += V^T P^T.  V is transposed on
-//   its way into LDS ([key quad][d][4 keys]) so that the V^T operand is two 8-byte LDS reads.
+//   cross-lane shuffles, and exp(S^T) is already the B operand of O^T += V^T P^T.  K and V stay
+//   row-major in LDS (XOR-swizzled 16 B / 32 B chunks instead of padding); the V^T operand comes from
+//   the transposing LDS read (ds_read_b64_tr_b16), Q fragments are re-read from a shared LDS copy.
 //   Every chunk writes an unnormalised fp32 partial (O, running max, sum); a second kernel merges the
 //   partials of a row in split order (deterministic) and writes bf16.
 #include "common.h"
@@ -21,13 +24,26 @@ namespace specv {
 
 constexpr int kD = 128;                      // head dimension
 constexpr int kP = 16;                       // tokens per page
-constexpr int kTile = 128;                   // keys per LDS tile
-constexpr int kKPitch = 272;                 // bytes per K row in LDS (256 + 16: 16 rows hit 16 distinct bank groups)
-constexpr int kVPitch = 1152;                // bytes per key quad in LDS ([128 d][4 keys] bf16 = 1024, + 128)
-constexpr int kKBytes = kTile * kKPitch;     // 34816
-constexpr int kVBytes = (kTile / 4) * kVPitch;   // 36864
+constexpr int kTile = 128;                   // keys per workgroup step (4 waves x 32)
+constexpr int kRowBytes = kD * 2;            // one K or V row in LDS (unpadded, swizzled)
+constexpr int kWaveLds = 2 * 32 * kRowBytes; // per wave: 32 K rows + 32 V rows = 16 KB
 constexpr int kRedPitch = 36;                // floats per row of the epilogue reduction buffer (32 + 4)
 constexpr float kNegBig = -1.0e30f;          // "nothing seen yet" running maximum (log2 domain)
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform)
+__device__ inline void lds_dma16(const void* g, void* lds_base)
+{
+    __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+
+// Transposing LDS read.  In every group of 16 lanes, lane r supplies the address of 4 consecutive
+// 16-bit elements M[r][0..3]; lane j receives M[j/4][j%4], M[4 + j/4][j%4], M[8 + j/4][j%4], M[12 + j/4][j%4].
+__device__ inline s16x4 lds_read_tr(const void* lds)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)lds);
+}
 
 struct AttnParams {
     const uint16_t* q;
@@ -53,13 +69,14 @@ template <int NR>
 __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* sK = smem;
-    unsigned char* sV = smem + kKBytes;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, i = blockIdx.z;
+    unsigned char* sK = smem + wave * kWaveLds;          // this wave's 32 K rows
+    unsigned char* sV = sK + 32 * kRowBytes;             // and 32 V rows
+    unsigned char* sQ = smem + 4 * kWaveLds;             // shared: NR*16 query rows
 
     const int r0 = p.qo_indptr[i], n = p.qo_indptr[i + 1] - r0, c = p.seq_lens[i];
     if (!request_ok(r0, n, c, p)) {
@@ -75,22 +92,23 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
     const int G = p.G, R = G * n;
     const int32_t* pt = p.page_table + (size_t)i * p.max_pages;
 
-    // ---- query fragments (B operand of S^T = K Q^T): lane (row l16, k-group g) holds d = 32s+8g..+7 ----
-    bf16x8 qf[NR][4];
+    // ---- query rows -> LDS (row r = j*G + gq; 16-byte chunk ch of row r sits at position ch ^ (r & 15)) ----
+    for (int idx = tid; idx < NR * 16 * 16; idx += 256) {
+        const int row = idx >> 4, ch = idx & 15;
+        u32x4 val = u32x4{0, 0, 0, 0};
+        if (row < R) {
+            const int j = row / G, gq = row - j * G;
+            val = *reinterpret_cast<const u32x4*>(p.q + ((size_t)(r0 + j) * p.Hq + kvh * G + gq) * kD + ch * 8);
+        }
+        *reinterpret_cast<u32x4*>(sQ + row * kRowBytes + ((ch ^ (row & 15)) << 4)) = val;
+    }
     int limit[NR];                    // row sees key positions t < limit
 #pragma unroll
     for (int rt = 0; rt < NR; ++rt) {
         const int r = rt * 16 + l16;
-        const bool live = r < R;
-        const int j = live ? r / G : 0, gq = live ? r - j * G : 0;
-        limit[rt] = live ? min(c + j + 1, kend) : 0;
-        const uint16_t* src = p.q + ((size_t)(r0 + j) * p.Hq + kvh * G + gq) * kD + g * 8;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            u32x4 t = live ? *reinterpret_cast<const u32x4*>(src + s * 32) : u32x4{0, 0, 0, 0};
-            qf[rt][s] = __builtin_bit_cast(bf16x8, t);
-        }
+        limit[rt] = (r < R) ? min(c + r / G + 1, kend) : 0;
     }
+    __syncthreads();
 
     f32x4 o[NR][8];
     float m_run[NR], l_run[NR];
@@ -102,152 +120,115 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
         for (int dt = 0; dt < 8; ++dt) o[rt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- global -> register staging of one tile: 8 x 16 B of K and 8 x 16 B of V per thread ----
-    u32x4 kreg[8], vreg[8];
     int bad_page = 0;
-    const int v_page_sub = tid >> 6;              // V: which of 4 pages of a pass this wave loads
-    const int v_quad = (tid & 63) >> 4, v_chunk = tid & 15;
-    auto fetch = [&](int tile_base) {
-        const int page0 = tile_base / kP;
+    const int drow = lane >> 4, dpos = lane & 15;        // direct-load role: row within a group of 4, 16-byte position
+    for (int wbase = kbeg + wave * 32; wbase < kend; wbase += kTile) {
+        // ---- this wave's two pages, K and V, HBM -> LDS ----
+        __builtin_amdgcn_s_waitcnt(0xC07F);               // lgkmcnt(0): the previous step's LDS reads have returned
 #pragma unroll
-        for (int pg = 0; pg < 8; ++pg) {
-            const int t0 = tile_base + pg * kP;
-            u32x4 val = u32x4{0, 0, 0, 0};
+        for (int pg = 0; pg < 2; ++pg) {
+            const int t0 = wbase + pg * kP;
             if (t0 < kend) {
-                const int page = pt[page0 + pg];
-                if (page >= 0 && page < p.num_pages)
-                    val = *reinterpret_cast<const u32x4*>(p.k_cache + ((size_t)page * p.Hkv + kvh) * (kP * kD) + tid * 8);
-                else
+                const int page = pt[t0 / kP];
+                if (page >= 0 && page < p.num_pages) {
+                    const size_t base = ((size_t)page * p.Hkv + kvh) * (kP * kD);
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const int row = q4 * 4 + drow;     // slot in the page = key & 15
+                        // K: chunk ch of a row is stored at position ch ^ (row & 15)
+                        lds_dma16(p.k_cache + base + row * kD + ((dpos ^ row) << 3), sK + (pg * 16 + q4 * 4) * kRowBytes);
+                        // V: 32-byte chunk c of a row is stored at position c ^ (row & 7)
+                        const int src16 = ((((dpos >> 1) ^ (row & 7)) << 1) | (dpos & 1));
+                        lds_dma16(p.v_cache + base + row * kD + (src16 << 3), sV + (pg * 16 + q4 * 4) * kRowBytes);
+                    }
+                } else {
                     bad_page = 1;
-            }
-            kreg[pg] = val;
-        }
-#pragma unroll
-        for (int ps = 0; ps < 2; ++ps) {
-            const int pg = ps * 4 + v_page_sub;
-            const int t0 = tile_base + pg * kP;
-            int page = -1;
-            if (t0 < kend) {
-                page = pt[page0 + pg];
-                if (page < 0 || page >= p.num_pages) page = -1;      // flagged by the K path
-            }
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int key = v_quad * 4 + kk;
-                u32x4 val = u32x4{0, 0, 0, 0};
-                if (page >= 0 && t0 + key < kend)                      // slots past the range may hold anything
-                    val = *reinterpret_cast<const u32x4*>(p.v_cache + ((size_t)page * p.Hkv + kvh) * (kP * kD) + key * kD + v_chunk * 8);
-                vreg[ps * 4 + kk] = val;
+                }
             }
         }
-    };
-    auto stash = [&]() {
-#pragma unroll
-        for (int pg = 0; pg < 8; ++pg) {
-            const int row = pg * kP + (tid >> 4);
-            *reinterpret_cast<u32x4*>(sK + row * kKPitch + (tid & 15) * 16) = kreg[pg];
-        }
-#pragma unroll
-        for (int ps = 0; ps < 2; ++ps) {
-            const int quad = (ps * 4 + v_page_sub) * 4 + v_quad;
-            unsigned char* dst = sV + quad * kVPitch + v_chunk * 64;
-            const u32x4 a = vreg[ps * 4 + 0], b = vreg[ps * 4 + 1], cc = vreg[ps * 4 + 2], d = vreg[ps * 4 + 3];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                // word w holds d = 2w (low half) and 2w+1 (high half) of each of the 4 keys
-                u32x4 outv;
-                outv.x = (a[w] & 0xFFFFu) | (b[w] << 16);
-                outv.y = (cc[w] & 0xFFFFu) | (d[w] << 16);
-                outv.z = (a[w] >> 16) | (b[w] & 0xFFFF0000u);
-                outv.w = (cc[w] >> 16) | (d[w] & 0xFFFF0000u);
-                *reinterpret_cast<u32x4*>(dst + w * 16) = outv;
+        __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): the pages have landed
+        if (wbase + 32 > kend) {
+            // slots past the range may hold anything (even NaN patterns): P is 0 there, so V must be too
+            for (int idx = lane; idx < 32 * 16; idx += 64) {
+                const int row = idx >> 4;
+                if (wbase + row >= kend) *reinterpret_cast<u32x4*>(sV + row * kRowBytes + (idx & 15) * 16) = u32x4{0, 0, 0, 0};
             }
         }
-    };
 
-    const int ntiles = (kend - kbeg + kTile - 1) / kTile;
-    if (ntiles > 0) fetch(kbeg);
-    for (int it = 0; it < ntiles; ++it) {
-        const int tile_base = kbeg + it * kTile;
-        __syncthreads();
-        stash();
-        __syncthreads();
-        if (it + 1 < ntiles) fetch(tile_base + kTile);
-
-        const int wbase = tile_base + wave * 32;           // first key of this wave's 32
-        if (wbase < kend) {
-            // ---- S^T = K Q^T for two 16-key blocks ----
-            f32x4 st[2][NR];
+        // ---- S^T = K Q^T for the wave's two 16-key blocks ----
+        bf16x8 kf[2][4];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                kf[kb][s] = *reinterpret_cast<const bf16x8*>(sK + (kb * 16 + l16) * kRowBytes + (((s * 4 + g) ^ l16) << 4));
+        const bool need_mask = wbase + 32 > min(c + 1, kend);
+        bf16x8 pf[NR];
+#pragma unroll
+        for (int rt = 0; rt < NR; ++rt) {
+            bf16x8 qf[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                qf[s] = *reinterpret_cast<const bf16x8*>(sQ + (rt * 16 + l16) * kRowBytes + (((s * 4 + g) ^ l16) << 4));
+            float sc[8];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                bf16x8 kf[4];
-                const unsigned char* krow = sK + (wave * 32 + kb * 16 + l16) * kKPitch + g * 16;
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s = 0; s < 4; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(krow + s * 64);
+                for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][s], qf[s], acc, 0, 0, 0);
 #pragma unroll
-                for (int rt = 0; rt < NR; ++rt) {
-                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[s], qf[rt][s], acc, 0, 0, 0);
-                    st[kb][rt] = acc;
-                }
+                for (int e = 0; e < 4; ++e) sc[kb * 4 + e] = acc[e] * p.scale_log2e;
             }
-            // ---- V^T fragments: lane (d = 16dt + l16, k-group g) holds keys 4g..4g+3 of both blocks ----
-            bf16x8 vf[8];
-            {
-                const unsigned char* v0 = sV + (wave * 8 + g) * kVPitch + l16 * 8;
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) {
-                    const u32x2 lo = *reinterpret_cast<const u32x2*>(v0 + dt * 128);
-                    const u32x2 hi = *reinterpret_cast<const u32x2*>(v0 + 4 * kVPitch + dt * 128);
-                    vf[dt] = __builtin_bit_cast(bf16x8, u32x4{lo.x, lo.y, hi.x, hi.y});
-                }
-            }
-            const bool need_mask = wbase + 32 > min(c + 1, kend);
-#pragma unroll
-            for (int rt = 0; rt < NR; ++rt) {
-                float sc[8];
+            bool vis[8];
+            if (need_mask) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) sc[kb * 4 + e] = st[kb][rt][e] * p.scale_log2e;
-                bool vis[8];
-                if (need_mask) {
+                    for (int e = 0; e < 4; ++e) {
+                        vis[kb * 4 + e] = (wbase + kb * 16 + g * 4 + e) < limit[rt];
+                        if (!vis[kb * 4 + e]) sc[kb * 4 + e] = kNegBig;
+                    }
+            } else {
 #pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
+                for (int e = 0; e < 8; ++e) vis[e] = true;
+            }
+            float tmax = sc[0];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            vis[kb * 4 + e] = (wbase + kb * 16 + g * 4 + e) < limit[rt];
-                            if (!vis[kb * 4 + e]) sc[kb * 4 + e] = kNegBig;
-                        }
-                } else {
+            for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[e]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(m_run[rt], tmax);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+            m_run[rt] = m_new;
+            float pr[8], psum = 0.0f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) vis[e] = true;
-                }
-                float tmax = sc[0];
+            for (int e = 0; e < 8; ++e) {
+                pr[e] = vis[e] ? __builtin_amdgcn_exp2f(sc[e] - m_new) : 0.0f;
+                psum += pr[e];
+            }
+            l_run[rt] = l_run[rt] * alpha + psum;
+            if (__any(alpha != 1.0f)) {
 #pragma unroll
-                for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[e]);
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-                tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-                const float m_new = fmaxf(m_run[rt], tmax);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
-                m_run[rt] = m_new;
-                float pr[8], psum = 0.0f;
+                for (int dt = 0; dt < 8; ++dt) o[rt][dt] *= alpha;
+            }
+            const u32x4 pw = u32x4{pack_bf16x2(pr[0], pr[1]), pack_bf16x2(pr[2], pr[3]),
+                                   pack_bf16x2(pr[4], pr[5]), pack_bf16x2(pr[6], pr[7])};
+            pf[rt] = __builtin_bit_cast(bf16x8, pw);
+        }
+        // ---- O^T += V^T P^T: lane (d = 16dt + l16, k-group g) needs keys 4g..4g+3 of both blocks at one d.
+        // For the transposing read, lane r of a group supplies key 4g + r/4, d = 16dt + 4*(r%4) .. +3. ----
+        {
+            const int vrow = 4 * g + (l16 >> 2);
+            const unsigned char* v0 = sV + vrow * kRowBytes + 8 * (l16 & 3);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    pr[e] = vis[e] ? __builtin_amdgcn_exp2f(sc[e] - m_new) : 0.0f;
-                    psum += pr[e];
-                }
-                l_run[rt] = l_run[rt] * alpha + psum;
-                if (__any(alpha != 1.0f)) {
+            for (int dt = 0; dt < 8; ++dt) {
+                const int off = (dt ^ (vrow & 7)) << 5;
+                const s16x4 lo = lds_read_tr(v0 + off);
+                const s16x4 hi = lds_read_tr(v0 + 16 * kRowBytes + off);
+                struct { s16x4 a, b; } pair = {lo, hi};
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, pair);
 #pragma unroll
-                    for (int dt = 0; dt < 8; ++dt) o[rt][dt] *= alpha;
-                }
-                const u32x4 pw = u32x4{pack_bf16x2(pr[0], pr[1]), pack_bf16x2(pr[2], pr[3]),
-                                       pack_bf16x2(pr[4], pr[5]), pack_bf16x2(pr[6], pr[7])};
-                const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf, o[rt][dt], 0, 0, 0);
+                for (int rt = 0; rt < NR; ++rt) o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], o[rt][dt], 0, 0, 0);
             }
         }
     }
@@ -356,7 +337,7 @@ static int attn_chunk_target(int B, int Hkv, int max_kv_len)
 
 static size_t attn_smem_bytes(int NR)
 {
-    const size_t tiles = kKBytes + kVBytes;
+    const size_t tiles = 4 * (size_t)kWaveLds + (size_t)NR * 16 * kRowBytes;
     const size_t epi = (size_t)(2 * 4 * NR * 16 + 4 * NR * 16 * kRedPitch) * sizeof(float);
     return tiles > epi ? tiles : epi;
 }
