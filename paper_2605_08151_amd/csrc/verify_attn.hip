@@ -24,18 +24,21 @@ namespace specv {
 
 constexpr int kD = 128;                      // head dimension
 constexpr int kP = 16;                       // tokens per page
-constexpr int kTile = 128;                   // keys per workgroup step (4 waves x 32)
 constexpr int kRowBytes = kD * 2;            // one K or V row in LDS (unpadded, swizzled)
 constexpr int kWaveLds = 2 * 32 * kRowBytes; // per wave: 32 K rows + 32 V rows = 16 KB
 constexpr int kRedPitch = 36;                // floats per row of the epilogue reduction buffer (32 + 4)
 constexpr float kNegBig = -1.0e30f;          // "nothing seen yet" running maximum (log2 domain)
+constexpr float kMaxSlack = 6.0f;            // how far a step's maximum may exceed the reference before a rescale
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform)
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
+// Written as inline assembly so that the compiler does not order it against later LDS reads by draining
+// the whole load queue: the kernel double-buffers and waits with explicit s_waitcnt vmcnt(n) instead.
 __device__ inline void lds_dma16(const void* g, void* lds_base)
 {
-    __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+    const uint32_t m0v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_base;
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0v) : "memory");
 }
 
 // Transposing LDS read.  In every group of 16 lanes, lane r supplies the address of 4 consecutive
@@ -52,11 +55,13 @@ struct AttnParams {
     const int32_t* page_table;
     const int32_t* seq_lens;
     const int32_t* qo_indptr;
+    uint16_t* out;      // [M, Hq, 128] bf16
+    float* lse;         // [M, Hq] or null
     float* part_o;      // [M*Hq, splits, 128]
     float* part_m;      // [M*Hq, splits]   running max, log2 domain
     float* part_l;      // [M*Hq, splits]
     int32_t* status_flags;
-    int max_pages, num_pages, Hq, Hkv, G, M, max_kv_len, max_q_len, chunk_target, splits;
+    int max_pages, num_pages, Hq, Hkv, G, M, max_kv_len, max_q_len, chunk_target, splits, dbg;
     float scale_log2e;
 };
 
@@ -65,18 +70,23 @@ __device__ inline bool request_ok(int r0, int n, int c, const AttnParams& p)
     return n >= 1 && n <= p.max_q_len && r0 >= 0 && r0 + n <= p.M && c >= 0 && c + n <= p.max_kv_len;
 }
 
-template <int NR>
-__global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
+// NR: 16-row query tiles per (request, kv head); NW: waves per workgroup (each owns 32 keys of a step);
+// FINAL: no request is split, so the workgroup normalises and writes bf16 itself (no partials, no merge kernel).
+// NBUF: K/V buffers per wave (2 = the next step's pages are in flight while this step is computed).
+template <int NR, int NW, int NBUF, bool FINAL>
+__global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
 {
+    constexpr int kThreads = NW * 64;
+    constexpr int kTile = NW * 32;                    // keys per workgroup step
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
     const int split = blockIdx.x, kvh = blockIdx.y, i = blockIdx.z;
-    unsigned char* sK = smem + wave * kWaveLds;          // this wave's 32 K rows
-    unsigned char* sV = sK + 32 * kRowBytes;             // and 32 V rows
-    unsigned char* sQ = smem + 4 * kWaveLds;             // shared: NR*16 query rows
+    unsigned char* sKV = smem + wave * (NBUF * kWaveLds); // this wave's NBUF x (32 K rows, 32 V rows)
+    unsigned char* sQ = smem + NW * NBUF * kWaveLds;      // shared: NR*16 query rows
+    int32_t* sPT = reinterpret_cast<int32_t*>(sQ + NR * 16 * kRowBytes);   // shared: page ids of this chunk
 
     const int r0 = p.qo_indptr[i], n = p.qo_indptr[i + 1] - r0, c = p.seq_lens[i];
     if (!request_ok(r0, n, c, p)) {
@@ -92,8 +102,44 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
     const int G = p.G, R = G * n;
     const int32_t* pt = p.page_table + (size_t)i * p.max_pages;
 
+    // ---- page ids of the chunk -> LDS, validated once (page 0 stands in for a bad id, which is flagged).
+    // Inside the loop they are read back from LDS: a global load there would sit in the same in-order
+    // queue as the direct K/V loads and force them to drain. ----
+    int bad_page = 0;
+    const int npages = (kend - kbeg + kP - 1) / kP;
+    for (int pg = tid; pg < npages; pg += kThreads) {
+        int page = pt[kbeg / kP + pg];
+        if (page < 0 || page >= p.num_pages) { page = 0; bad_page = 1; }
+        sPT[pg] = page;
+    }
+    __syncthreads();
+
+    // ---- this wave's two pages of a step, K and V, HBM -> LDS (always 16 direct loads: positions past the
+    // range read page 0 instead, so the wait counts below are constants) ----
+    const int drow = lane >> 4, dpos = lane & 15;        // direct-load role: row within a group of 4, 16-byte position
+    auto issue_step = [&](int wbase, unsigned char* buf) {
+        if (p.dbg & 1) return;
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+            const int t0 = wbase + pg * kP;
+            const int page = (t0 < kend) ? __builtin_amdgcn_readfirstlane(sPT[(t0 - kbeg) / kP]) : 0;
+            const size_t base = ((size_t)page * p.Hkv + kvh) * (kP * kD);
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int row = q4 * 4 + drow;             // slot in the page = key & 15
+                // K: chunk ch of a row is stored at position ch ^ (row & 15)
+                lds_dma16(p.k_cache + base + row * kD + ((dpos ^ row) << 3), buf + (pg * 16 + q4 * 4) * kRowBytes);
+                // V: 32-byte chunk c of a row is stored at position c ^ (row & 7)
+                const int src16 = ((((dpos >> 1) ^ (row & 7)) << 1) | (dpos & 1));
+                lds_dma16(p.v_cache + base + row * kD + (src16 << 3), buf + (32 + pg * 16 + q4 * 4) * kRowBytes);
+            }
+        }
+    };
+    const int wfirst = kbeg + wave * 32;
+    if (wfirst < kend) issue_step(wfirst, sKV);           // in flight while Q is staged
+
     // ---- query rows -> LDS (row r = j*G + gq; 16-byte chunk ch of row r sits at position ch ^ (r & 15)) ----
-    for (int idx = tid; idx < NR * 16 * 16; idx += 256) {
+    for (int idx = tid; idx < NR * 16 * 16; idx += kThreads) {
         const int row = idx >> 4, ch = idx & 15;
         u32x4 val = u32x4{0, 0, 0, 0};
         if (row < R) {
@@ -120,33 +166,26 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
         for (int dt = 0; dt < 8; ++dt) o[rt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    int bad_page = 0;
-    const int drow = lane >> 4, dpos = lane & 15;        // direct-load role: row within a group of 4, 16-byte position
-    for (int wbase = kbeg + wave * 32; wbase < kend; wbase += kTile) {
-        // ---- this wave's two pages, K and V, HBM -> LDS ----
-        __builtin_amdgcn_s_waitcnt(0xC07F);               // lgkmcnt(0): the previous step's LDS reads have returned
-#pragma unroll
-        for (int pg = 0; pg < 2; ++pg) {
-            const int t0 = wbase + pg * kP;
-            if (t0 < kend) {
-                const int page = pt[t0 / kP];
-                if (page >= 0 && page < p.num_pages) {
-                    const size_t base = ((size_t)page * p.Hkv + kvh) * (kP * kD);
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const int row = q4 * 4 + drow;     // slot in the page = key & 15
-                        // K: chunk ch of a row is stored at position ch ^ (row & 15)
-                        lds_dma16(p.k_cache + base + row * kD + ((dpos ^ row) << 3), sK + (pg * 16 + q4 * 4) * kRowBytes);
-                        // V: 32-byte chunk c of a row is stored at position c ^ (row & 7)
-                        const int src16 = ((((dpos >> 1) ^ (row & 7)) << 1) | (dpos & 1));
-                        lds_dma16(p.v_cache + base + row * kD + (src16 << 3), sV + (pg * 16 + q4 * 4) * kRowBytes);
-                    }
-                } else {
-                    bad_page = 1;
-                }
+    int it = 0;
+    for (int wbase = wfirst; wbase < kend; wbase += kTile, ++it) {
+        unsigned char* sK = sKV + (NBUF == 2 ? (it & 1) * kWaveLds : 0);
+        unsigned char* sV = sK + 32 * kRowBytes;
+        if (NBUF == 2) {
+            // the other buffer was last read in the previous step; its reads have returned
+            __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0)
+            if (wbase + kTile < kend) {
+                issue_step(wbase + kTile, sKV + ((it + 1) & 1) * kWaveLds);
+                __builtin_amdgcn_s_waitcnt(0x4F70);       // vmcnt(16): this step's pages have landed, the next 16 loads fly on
+            } else {
+                __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
             }
+        } else {
+            if (it > 0) {
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): the previous step's LDS reads have returned
+                issue_step(wbase, sKV);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this step's pages have landed
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): the pages have landed
         if (wbase + 32 > kend) {
             // slots past the range may hold anything (even NaN patterns): P is 0 there, so V must be too
             for (int idx = lane; idx < 32 * 16; idx += 64) {
@@ -155,6 +194,7 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
             }
         }
 
+        if (p.dbg & 2) continue;
         // ---- S^T = K Q^T for the wave's two 16-key blocks ----
         bf16x8 kf[2][4];
 #pragma unroll
@@ -163,54 +203,79 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
             for (int s = 0; s < 4; ++s)
                 kf[kb][s] = *reinterpret_cast<const bf16x8*>(sK + (kb * 16 + l16) * kRowBytes + (((s * 4 + g) ^ l16) << 4));
         const bool need_mask = wbase + 32 > min(c + 1, kend);
-        bf16x8 pf[NR];
+        // The row tiles go through every phase together (scores, maxima, exponentials) so that the
+        // dependent chains of different tiles (MFMA -> max -> cross-lane max -> exp) overlap in the one wave.
+        float sc[NR][8];
 #pragma unroll
         for (int rt = 0; rt < NR; ++rt) {
             bf16x8 qf[4];
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 qf[s] = *reinterpret_cast<const bf16x8*>(sQ + (rt * 16 + l16) * kRowBytes + (((s * 4 + g) ^ l16) << 4));
-            float sc[8];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][s], qf[s], acc, 0, 0, 0);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) sc[kb * 4 + e] = acc[e] * p.scale_log2e;
+                for (int e = 0; e < 4; ++e) sc[rt][kb * 4 + e] = acc[e] * p.scale_log2e;
             }
-            bool vis[8];
-            if (need_mask) {
+        }
+        if (need_mask) {
+#pragma unroll
+            for (int rt = 0; rt < NR; ++rt)
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        vis[kb * 4 + e] = (wbase + kb * 16 + g * 4 + e) < limit[rt];
-                        if (!vis[kb * 4 + e]) sc[kb * 4 + e] = kNegBig;
-                    }
-            } else {
+                    for (int e = 0; e < 4; ++e)
+                        if ((wbase + kb * 16 + g * 4 + e) >= limit[rt]) sc[rt][kb * 4 + e] = kNegBig;   // exp2 of it is 0
+        }
+        float tmax[NR];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) vis[e] = true;
+        for (int rt = 0; rt < NR; ++rt) {
+            float t = sc[rt][0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e) t = fmaxf(t, sc[rt][e]);
+            tmax[rt] = t;
+        }
+#pragma unroll
+        for (int rt = 0; rt < NR; ++rt) tmax[rt] = fmaxf(tmax[rt], __shfl_xor(tmax[rt], 16, 64));
+#pragma unroll
+        for (int rt = 0; rt < NR; ++rt) tmax[rt] = fmaxf(tmax[rt], __shfl_xor(tmax[rt], 32, 64));
+        // Lazy reference maximum: m_run only moves when a step's maximum exceeds it by more than kMaxSlack
+        // (log2 units), so exp2(s - m_run) <= 2^kMaxSlack stays well inside fp32/bf16 range and the 32
+        // accumulator registers of a row tile are rescaled a handful of times per chunk instead of almost
+        // every step.  The result is the same softmax: O and l carry the same factor.
+        bool grow = false;
+#pragma unroll
+        for (int rt = 0; rt < NR; ++rt) grow |= tmax[rt] > m_run[rt] + kMaxSlack;
+        if (__any(grow)) {
+#pragma unroll
+            for (int rt = 0; rt < NR; ++rt) {
+                if (__any(tmax[rt] > m_run[rt] + kMaxSlack)) {
+                    const float m_new = fmaxf(m_run[rt], tmax[rt]);
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
+                    m_run[rt] = m_new;
+                    l_run[rt] *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt) o[rt][dt] *= alpha;
+                }
             }
-            float tmax = sc[0];
+        }
+        bf16x8 pf[NR];
 #pragma unroll
-            for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[e]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(m_run[rt], tmax);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
-            m_run[rt] = m_new;
+        for (int rt = 0; rt < NR; ++rt) {
+            const float m_ref = m_run[rt];
             float pr[8], psum = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                pr[e] = vis[e] ? __builtin_amdgcn_exp2f(sc[e] - m_new) : 0.0f;
+                // a masked score is kNegBig: exp2(kNegBig - m_ref) is 0 unless the row has seen nothing at all
+                // (m_ref == kNegBig), and such a row is masked by the comparison
+                pr[e] = __builtin_amdgcn_exp2f(sc[rt][e] - m_ref);
+                if (need_mask) pr[e] = (sc[rt][e] > 0.5f * kNegBig) ? pr[e] : 0.0f;
                 psum += pr[e];
             }
-            l_run[rt] = l_run[rt] * alpha + psum;
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) o[rt][dt] *= alpha;
-            }
+            l_run[rt] += psum;
             const u32x4 pw = u32x4{pack_bf16x2(pr[0], pr[1]), pack_bf16x2(pr[2], pr[3]),
                                    pack_bf16x2(pr[4], pr[5]), pack_bf16x2(pr[6], pr[7])};
             pf[rt] = __builtin_bit_cast(bf16x8, pw);
@@ -232,13 +297,16 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
             }
         }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                   // nothing of this wave is still landing in LDS
     if (bad_page && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_PAGE);
 
-    // ---- merge the 4 waves: common maximum, then O in 4 slices of 32 d through LDS ----
-    __syncthreads();                                      // tile buffers are free
-    float* s_m = reinterpret_cast<float*>(smem);          // [4][NR*16]
-    float* s_l = s_m + 4 * NR * 16;                       // [4][NR*16]
-    float* s_red = s_l + 4 * NR * 16;                     // [4][NR*16][kRedPitch]
+    // ---- merge the waves: common maximum, then O in 4 slices of 32 d through LDS ----
+    __syncthreads();                                      // every wave is done with its K/V rows and with Q
+    float* s_m = reinterpret_cast<float*>(smem);          // [NW][NR*16]
+    float* s_l = s_m + NW * NR * 16;                      // [NW][NR*16]
+    float* s_mx = s_l + NW * NR * 16;                     // [NR*16] merged maximum
+    float* s_lt = s_mx + NR * 16;                         // [NR*16] merged sum
+    float* s_red = s_lt + NR * 16;                        // [NW][NR*16][kRedPitch]
 #pragma unroll
     for (int rt = 0; rt < NR; ++rt) {
         float l = l_run[rt];
@@ -250,14 +318,20 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
         }
     }
     __syncthreads();
-    float fscale[NR];
-#pragma unroll
-    for (int rt = 0; rt < NR; ++rt) {
+    for (int r = tid; r < NR * 16; r += kThreads) {
         float mx = kNegBig;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) mx = fmaxf(mx, s_m[w * NR * 16 + rt * 16 + l16]);
-        fscale[rt] = exp2f(m_run[rt] - mx);
+        for (int w = 0; w < NW; ++w) mx = fmaxf(mx, s_m[w * NR * 16 + r]);
+        float l = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) l += s_l[w * NR * 16 + r] * exp2f(s_m[w * NR * 16 + r] - mx);
+        s_mx[r] = mx;
+        s_lt[r] = l;
     }
+    __syncthreads();
+    float fscale[NR];
+#pragma unroll
+    for (int rt = 0; rt < NR; ++rt) fscale[rt] = exp2f(m_run[rt] - s_mx[rt * 16 + l16]);
     // rows of this unit: r = j*G + gq  ->  global (row r0+j, head kvh*G+gq)
     const size_t unit_stride = (size_t)p.splits;
 #pragma unroll
@@ -270,34 +344,35 @@ __global__ __launch_bounds__(256) void verify_attn_kernel(AttnParams p)
                 *reinterpret_cast<f32x4*>(s_red + ((size_t)(wave * NR * 16 + rt * 16 + l16)) * kRedPitch + half * 16 + g * 4) = v;
             }
         __syncthreads();
-        for (int e = tid; e < R * 32; e += 256) {
+        for (int e = tid; e < R * 32; e += kThreads) {
             const int r = e >> 5, dl = e & 31;
             float sum = 0.0f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) sum += s_red[(size_t)(w * NR * 16 + r) * kRedPitch + dl];
+            for (int w = 0; w < NW; ++w) sum += s_red[(size_t)(w * NR * 16 + r) * kRedPitch + dl];
             const int j = r / G, gq = r - j * G;
-            const size_t unit = ((size_t)(r0 + j) * p.Hq + kvh * G + gq) * unit_stride + split;
-            p.part_o[unit * kD + ds * 32 + dl] = sum;
+            const size_t rowhead = (size_t)(r0 + j) * p.Hq + kvh * G + gq;
+            if (FINAL) p.out[rowhead * kD + ds * 32 + dl] = (uint16_t)f32_to_bf16_bits(sum / s_lt[r]);
+            else p.part_o[(rowhead * unit_stride + split) * kD + ds * 32 + dl] = sum;
         }
         __syncthreads();
     }
-    for (int r = tid; r < R; r += 256) {
-        float mx = kNegBig;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) mx = fmaxf(mx, s_m[w * NR * 16 + r]);
-        float l = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) l += s_l[w * NR * 16 + r] * exp2f(s_m[w * NR * 16 + r] - mx);
+    for (int r = tid; r < R; r += kThreads) {
         const int j = r / G, gq = r - j * G;
-        const size_t unit = ((size_t)(r0 + j) * p.Hq + kvh * G + gq) * unit_stride + split;
-        p.part_m[unit] = mx;
-        p.part_l[unit] = l;
+        const size_t rowhead = (size_t)(r0 + j) * p.Hq + kvh * G + gq;
+        if (FINAL) {
+            if (p.lse) p.lse[rowhead] = (s_mx[r] + log2f(s_lt[r])) * 0.6931471805599453f;
+        } else {
+            p.part_m[rowhead * unit_stride + split] = s_mx[r];
+            p.part_l[rowhead * unit_stride + split] = s_lt[r];
+        }
     }
 }
 
 // Merge the split partials of one (row, head) in split order and write bf16 (and lse).
-__global__ __launch_bounds__(128) void verify_attn_combine_kernel(AttnParams p, uint16_t* __restrict__ out, float* __restrict__ lse, int B)
+__global__ __launch_bounds__(128) void verify_attn_combine_kernel(AttnParams p, int B)
 {
+    uint16_t* __restrict__ out = p.out;
+    float* __restrict__ lse = p.lse;
     const int row = blockIdx.x, hq = blockIdx.y, d = threadIdx.x;
     int lo = 0, hi = B - 1;
     while (lo < hi) {
@@ -324,37 +399,76 @@ __global__ __launch_bounds__(128) void verify_attn_combine_kernel(AttnParams p, 
 }
 
 int g_attn_chunk_override = 0;
+int g_attn_dbg = 0;
 
-static int attn_chunk_target(int B, int Hkv, int max_kv_len)
+static int attn_cu_count()
 {
-    if (g_attn_chunk_override > 0) return (g_attn_chunk_override + kTile - 1) / kTile * kTile;
-    // aim at ~1024 workgroups when every request is as long as the bound, chunks of 256..4096 keys
-    long target = (long)B * Hkv * (long)max_kv_len / 1024;
-    if (target < 256) target = 256;
-    if (target > 4096) target = 4096;
-    return (int)((target + kTile - 1) / kTile * kTile);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
 }
 
-static size_t attn_smem_bytes(int NR)
+// Keys per kv split.  A split costs a prologue (Q to LDS), an epilogue (cross-wave merge) and a partial
+// that the merge kernel re-reads, so requests are only split when there are too few (request, kv head)
+// units to fill the chip or when they are long enough for the length spread to unbalance it.
+static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
 {
-    const size_t tiles = 4 * (size_t)kWaveLds + (size_t)NR * 16 * kRowBytes;
-    const size_t epi = (size_t)(2 * 4 * NR * 16 + 4 * NR * 16 * kRedPitch) * sizeof(float);
+    long target;
+    if (g_attn_chunk_override > 0) {
+        target = g_attn_chunk_override;
+    } else {
+        const long units = (long)B * Hkv, cus = attn_cu_count();
+        if (units >= cus && max_kv_len <= 4096) {
+            target = max_kv_len;                                   // one workgroup per unit, no merge kernel
+        } else {
+            target = units * (long)max_kv_len / (4 * cus);         // ~4 workgroups per CU at the length bound
+            if (target < 512) target = 512;
+            if (target > 4096) target = 4096;
+        }
+    }
+    if (target > 8192) target = 8192;                             // page ids of a chunk live in LDS (2 KB)
+    return (int)((target + step_keys - 1) / step_keys * step_keys);
+}
+
+static int attn_waves(int NR) { return NR <= 2 ? 8 : 4; }      // 8 waves need <= 256 registers per lane
+
+static size_t attn_smem_bytes(int NR, int NW, int NBUF, int chunk_keys)
+{
+    const size_t tiles = (size_t)NW * NBUF * kWaveLds + (size_t)NR * 16 * kRowBytes + (size_t)(chunk_keys / kP + 1) * 4;
+    const size_t epi = (size_t)(2 * NW * NR * 16 + 2 * NR * 16 + NW * NR * 16 * kRedPitch) * sizeof(float);
     return tiles > epi ? tiles : epi;
+}
+
+template <int NR, int NW, int NBUF, bool FINAL>
+static int launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t s)
+{
+    const size_t smem = attn_smem_bytes(NR, NW, NBUF, p.chunk_target < p.max_kv_len ? p.chunk_target : p.max_kv_len);
+    static size_t configured = 0;
+    if (configured < smem) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_attn_kernel<NR, NW, NBUF, FINAL>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return fail(SPEC_EHIP, "spec_verify_attn: cannot reserve %zu bytes of LDS", smem);
+        configured = smem;
+    }
+    hipLaunchKernelGGL((verify_attn_kernel<NR, NW, NBUF, FINAL>), grid, dim3(NW * 64), smem, s, p);
+    return SPEC_OK;
 }
 
 template <int NR>
 static int launch_attn(const AttnParams& p, dim3 grid, hipStream_t s)
 {
-    const size_t smem = attn_smem_bytes(NR);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_attn_kernel<NR>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return fail(SPEC_EHIP, "spec_verify_attn: cannot reserve %zu bytes of LDS", smem);
-        configured = true;
-    }
-    hipLaunchKernelGGL(verify_attn_kernel<NR>, grid, dim3(256), smem, s, p);
-    return SPEC_OK;
+    // up to 32 query rows: 8 waves (two per SIMD hide each other's loads, one K/V buffer per wave);
+    // more rows need > 256 registers per lane: 4 waves, each double-buffering its own pages
+    constexpr int NW = NR <= 2 ? 8 : 4;
+    constexpr int NBUF = (NR <= 2 || NR >= 7) ? 1 : 2;   // 7-8 row tiles leave no LDS for a second buffer
+    return p.splits == 1 ? launch_attn_one<NR, NW, NBUF, true>(p, grid, s) : launch_attn_one<NR, NW, NBUF, false>(p, grid, s);
 }
 
 }  // namespace specv
@@ -362,9 +476,11 @@ static int launch_attn(const AttnParams& p, dim3 grid, hipStream_t s)
 extern "C" size_t spec_verify_attn_workspace_bytes(int B, int M, int Hq, int Hkv, int D, int max_kv_len, int max_q_len)
 {
     using namespace specv;
-    (void)D; (void)max_q_len;
-    if (B <= 0 || M <= 0 || Hq <= 0 || Hkv <= 0 || max_kv_len <= 0) return 0;
-    const int ct = attn_chunk_target(B, Hkv, max_kv_len);
+    (void)D;
+    if (B <= 0 || M <= 0 || Hq <= 0 || Hkv <= 0 || max_kv_len <= 0 || Hq % Hkv != 0) return 0;
+    const int G = Hq / Hkv;
+    const int NR = (G * (max_q_len > 0 ? max_q_len : 1) + 15) / 16;
+    const int ct = attn_chunk_target(B, Hkv, max_kv_len, attn_waves(NR) * 32);
     const size_t splits = (size_t)(max_kv_len + ct - 1) / ct;
     const size_t units = (size_t)M * Hq * splits;
     return round_up(units * kD * 4, 256) + 2 * round_up(units * 4, 256);
@@ -406,8 +522,9 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
     p.page_table = page_table; p.seq_lens = seq_lens; p.qo_indptr = qo_indptr;
     p.status_flags = status_flags;
     p.max_pages = max_pages_per_seq; p.num_pages = num_pages; p.Hq = Hq; p.Hkv = Hkv; p.G = G;
-    p.M = M; p.max_kv_len = max_kv_len; p.max_q_len = max_q_len;
-    p.chunk_target = attn_chunk_target(B, Hkv, max_kv_len);
+    p.dbg = g_attn_dbg; p.M = M; p.max_kv_len = max_kv_len; p.max_q_len = max_q_len;
+    p.chunk_target = attn_chunk_target(B, Hkv, max_kv_len, attn_waves(NR) * 32);
+    p.out = (uint16_t*)out; p.lse = lse;
     p.splits = (max_kv_len + p.chunk_target - 1) / p.chunk_target;
     p.scale_log2e = scale * 1.4426950408889634f;
     const size_t units = (size_t)M * Hq * p.splits;
@@ -432,6 +549,7 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
     if (rc != SPEC_OK) return rc;
     rc = check_launch("spec_verify_attn");
     if (rc != SPEC_OK) return rc;
-    hipLaunchKernelGGL(verify_attn_combine_kernel, dim3(M, Hq), dim3(128), 0, s, p, (uint16_t*)out, lse, B);
+    if (p.splits == 1) return SPEC_OK;                    // the main kernel wrote the output itself
+    hipLaunchKernelGGL(verify_attn_combine_kernel, dim3(M, Hq), dim3(128), 0, s, p, B);
     return check_launch("spec_verify_attn (combine)");
 }
