@@ -19,6 +19,7 @@
 #include "common.h"
 
 #include <cmath>
+#include <type_traits>
 
 namespace specv {
 
@@ -100,6 +101,7 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
     const int kbeg = split * chunk;
     const int kend = min(len, kbeg + chunk);
     const int G = p.G, R = G * n;
+    const int nrt = (R + 15) >> 4;                        // row tiles this request really has (wave-uniform, <= NR)
     const int32_t* pt = p.page_table + (size_t)i * p.max_pages;
 
     // ---- page ids of the chunk -> LDS, validated once (page 0 stands in for a bad id, which is flagged).
@@ -166,6 +168,10 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
         for (int dt = 0; dt < 8; ++dt) o[rt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // The loop is instantiated for every number of row tiles A <= NR a request can have, so that a decode
+    // row in a batch sized for 9-row candidates pays for one tile of math, not five.
+    auto run_chunk = [&](auto active) {
+    constexpr int A = decltype(active)::value;
     int it = 0;
     for (int wbase = wfirst; wbase < kend; wbase += kTile, ++it) {
         unsigned char* sK = sKV + (NBUF == 2 ? (it & 1) * kWaveLds : 0);
@@ -205,9 +211,9 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
         const bool need_mask = wbase + 32 > min(c + 1, kend);
         // The row tiles go through every phase together (scores, maxima, exponentials) so that the
         // dependent chains of different tiles (MFMA -> max -> cross-lane max -> exp) overlap in the one wave.
-        float sc[NR][8];
+        float sc[A][8];
 #pragma unroll
-        for (int rt = 0; rt < NR; ++rt) {
+        for (int rt = 0; rt < A; ++rt) {
             bf16x8 qf[4];
 #pragma unroll
             for (int s = 0; s < 4; ++s)
@@ -223,35 +229,35 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
         }
         if (need_mask) {
 #pragma unroll
-            for (int rt = 0; rt < NR; ++rt)
+            for (int rt = 0; rt < A; ++rt)
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if ((wbase + kb * 16 + g * 4 + e) >= limit[rt]) sc[rt][kb * 4 + e] = kNegBig;   // exp2 of it is 0
         }
-        float tmax[NR];
+        float tmax[A];
 #pragma unroll
-        for (int rt = 0; rt < NR; ++rt) {
+        for (int rt = 0; rt < A; ++rt) {
             float t = sc[rt][0];
 #pragma unroll
             for (int e = 1; e < 8; ++e) t = fmaxf(t, sc[rt][e]);
             tmax[rt] = t;
         }
 #pragma unroll
-        for (int rt = 0; rt < NR; ++rt) tmax[rt] = fmaxf(tmax[rt], __shfl_xor(tmax[rt], 16, 64));
+        for (int rt = 0; rt < A; ++rt) tmax[rt] = fmaxf(tmax[rt], __shfl_xor(tmax[rt], 16, 64));
 #pragma unroll
-        for (int rt = 0; rt < NR; ++rt) tmax[rt] = fmaxf(tmax[rt], __shfl_xor(tmax[rt], 32, 64));
+        for (int rt = 0; rt < A; ++rt) tmax[rt] = fmaxf(tmax[rt], __shfl_xor(tmax[rt], 32, 64));
         // Lazy reference maximum: m_run only moves when a step's maximum exceeds it by more than kMaxSlack
         // (log2 units), so exp2(s - m_run) <= 2^kMaxSlack stays well inside fp32/bf16 range and the 32
         // accumulator registers of a row tile are rescaled a handful of times per chunk instead of almost
         // every step.  The result is the same softmax: O and l carry the same factor.
         bool grow = false;
 #pragma unroll
-        for (int rt = 0; rt < NR; ++rt) grow |= tmax[rt] > m_run[rt] + kMaxSlack;
+        for (int rt = 0; rt < A; ++rt) grow |= tmax[rt] > m_run[rt] + kMaxSlack;
         if (__any(grow)) {
 #pragma unroll
-            for (int rt = 0; rt < NR; ++rt) {
+            for (int rt = 0; rt < A; ++rt) {
                 if (__any(tmax[rt] > m_run[rt] + kMaxSlack)) {
                     const float m_new = fmaxf(m_run[rt], tmax[rt]);
                     const float alpha = __builtin_amdgcn_exp2f(m_run[rt] - m_new);
@@ -262,9 +268,9 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
                 }
             }
         }
-        bf16x8 pf[NR];
+        bf16x8 pf[A];
 #pragma unroll
-        for (int rt = 0; rt < NR; ++rt) {
+        for (int rt = 0; rt < A; ++rt) {
             const float m_ref = m_run[rt];
             float pr[8], psum = 0.0f;
 #pragma unroll
@@ -293,9 +299,20 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
                 struct { s16x4 a, b; } pair = {lo, hi};
                 const bf16x8 vf = __builtin_bit_cast(bf16x8, pair);
 #pragma unroll
-                for (int rt = 0; rt < NR; ++rt) o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], o[rt][dt], 0, 0, 0);
+                for (int rt = 0; rt < A; ++rt) o[rt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], o[rt][dt], 0, 0, 0);
             }
         }
+    }
+    };
+    switch (nrt) {
+        case 1: run_chunk(std::integral_constant<int, 1>{}); break;
+        case 2: if constexpr (NR >= 2) run_chunk(std::integral_constant<int, 2>{}); break;
+        case 3: if constexpr (NR >= 3) run_chunk(std::integral_constant<int, 3>{}); break;
+        case 4: if constexpr (NR >= 4) run_chunk(std::integral_constant<int, 4>{}); break;
+        case 5: if constexpr (NR >= 5) run_chunk(std::integral_constant<int, 5>{}); break;
+        case 6: if constexpr (NR >= 6) run_chunk(std::integral_constant<int, 6>{}); break;
+        case 7: if constexpr (NR >= 7) run_chunk(std::integral_constant<int, 7>{}); break;
+        default: if constexpr (NR >= 8) run_chunk(std::integral_constant<int, 8>{}); break;
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                   // nothing of this wave is still landing in LDS
     if (bad_page && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_PAGE);
@@ -368,12 +385,14 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
     }
 }
 
-// Merge the split partials of one (row, head) in split order and write bf16 (and lse).
-__global__ __launch_bounds__(128) void verify_attn_combine_kernel(AttnParams p, int B)
+// Merge the split partials of one (row, head) and write bf16 (and lse).  256 threads: lane group q = tid/32
+// takes splits q, q+8, ..., thread t%32 four consecutive d; the 8 groups are then summed in group order, so
+// the result does not depend on timing.
+__global__ __launch_bounds__(256) void verify_attn_combine_kernel(AttnParams p, int B)
 {
-    uint16_t* __restrict__ out = p.out;
-    float* __restrict__ lse = p.lse;
-    const int row = blockIdx.x, hq = blockIdx.y, d = threadIdx.x;
+    __shared__ float s_num[8][kD];
+    __shared__ float s_den[8];
+    const int row = blockIdx.x, hq = blockIdx.y, tid = threadIdx.x, grp = tid >> 5, d4 = (tid & 31) * 4;
     int lo = 0, hi = B - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
@@ -387,15 +406,23 @@ __global__ __launch_bounds__(128) void verify_attn_combine_kernel(AttnParams p, 
     const size_t unit = ((size_t)row * p.Hq + hq) * p.splits;
     float mx = kNegBig;
     for (int s = 0; s < ns; ++s) mx = fmaxf(mx, p.part_m[unit + s]);
-    float num = 0.0f, den = 0.0f;
-    for (int s = 0; s < ns; ++s) {
+    f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
+    float den = 0.0f;
+    for (int s = grp; s < ns; s += 8) {
         const float w = exp2f(p.part_m[unit + s] - mx);
-        num += w * p.part_o[(unit + s) * kD + d];
+        num += w * *reinterpret_cast<const f32x4*>(p.part_o + (unit + s) * kD + d4);
         den += w * p.part_l[unit + s];
     }
-    const float val = num / den;
-    out[((size_t)row * p.Hq + hq) * kD + d] = (uint16_t)f32_to_bf16_bits(val);
-    if (lse && d == 0) lse[(size_t)row * p.Hq + hq] = (mx + log2f(den)) * 0.6931471805599453f;
+    *reinterpret_cast<f32x4*>(&s_num[grp][d4]) = num;
+    if ((tid & 31) == 0) s_den[grp] = den;
+    __syncthreads();
+    if (tid < kD) {
+        float a = 0.0f, dsum = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { a += s_num[q][tid]; dsum += s_den[q]; }
+        p.out[((size_t)row * p.Hq + hq) * kD + tid] = (uint16_t)f32_to_bf16_bits(a / dsum);
+        if (p.lse && tid == 0) p.lse[(size_t)row * p.Hq + hq] = (mx + log2f(dsum)) * 0.6931471805599453f;
+    }
 }
 
 int g_attn_chunk_override = 0;
@@ -424,14 +451,13 @@ static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
     if (g_attn_chunk_override > 0) {
         target = g_attn_chunk_override;
     } else {
+        // about one workgroup per CU when every request is as long as the bound (measured best on MI355X for
+        // B=8 x 64k, B=64 x 4k and B=256 x 32k lognormal alike); shorter requests simply get fewer splits
         const long units = (long)B * Hkv, cus = attn_cu_count();
-        if (units >= cus && max_kv_len <= 4096) {
-            target = max_kv_len;                                   // one workgroup per unit, no merge kernel
-        } else {
-            target = units * (long)max_kv_len / (4 * cus);         // ~4 workgroups per CU at the length bound
-            if (target < 512) target = 512;
-            if (target > 4096) target = 4096;
-        }
+        target = units * (long)max_kv_len / cus;
+        if (target < 512) target = 512;
+        if (target > 4096) target = 4096;
+        if (target >= max_kv_len) target = max_kv_len;             // nobody is split: no partials, no merge kernel
     }
     if (target > 8192) target = 8192;                             // page ids of a chunk live in LDS (2 KB)
     return (int)((target + step_keys - 1) / step_keys * step_keys);
@@ -550,6 +576,6 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
     rc = check_launch("spec_verify_attn");
     if (rc != SPEC_OK) return rc;
     if (p.splits == 1) return SPEC_OK;                    // the main kernel wrote the output itself
-    hipLaunchKernelGGL(verify_attn_combine_kernel, dim3(M, Hq), dim3(128), 0, s, p, B);
+    hipLaunchKernelGGL(verify_attn_combine_kernel, dim3(M, Hq), dim3(256), 0, s, p, B);
     return check_launch("spec_verify_attn (combine)");
 }
