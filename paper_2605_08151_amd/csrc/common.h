@@ -53,4 +53,13 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
+// Written as inline assembly so that the compiler does not order it against later LDS reads by draining
+// the whole load queue: the kernel double-buffers and waits with explicit s_waitcnt vmcnt(n) instead.
+__device__ inline void lds_dma16(const void* g, void* lds_base)
+{
+    const uint32_t m0v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_base;
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0v) : "memory");
+}
+
 }  // namespace specv

@@ -264,6 +264,129 @@ __global__ __launch_bounds__(256, 1) void lm_head_skinny_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// MFMA-bound kernel for M > 160 rows (BASELINE configs 3 and 5: 576 and ~1152 rows).
+//   * (64*TMW) x 256 output tile per workgroup, 4 waves in a 2 x 2 grid, each wave TMW x 4 tiles of
+//     v_mfma_f32_32x32x16_bf16 (up to 256 accumulator registers).
+//   * K advances in slabs of 32 through a ring of 4 LDS stages filled by direct HBM/L2 -> LDS loads
+//     (no staging registers): three slabs are in flight while one is multiplied, one barrier per slab.
+//     Rows are 64 B in LDS with the 16-byte chunks XOR-swizzled by row pair, so the 8 lanes that read
+//     8 consecutive rows at the same k hit 8 different bank groups.
+//   * Workgroup -> tile mapping keeps the row tiles of one vocabulary tile on the same XCD (workgroups
+//     are dealt round-robin to the 8 XCDs), so a W slab is fetched into one L2 only.
+// ------------------------------------------------------------------------------------------------
+constexpr int kBigBN = 256, kBigBK = 32, kBigStages = 4;
+
+template <int TMW>
+__global__ __launch_bounds__(256, 1) void lm_head_big_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
+    int M, int H, int V, int tiles_m, int tiles_n)
+{
+    constexpr int BM = 64 * TMW;
+    constexpr int kRowB = kBigBK * 2;                     // 64 bytes per LDS row
+    constexpr int kRows = BM + kBigBN;
+    constexpr int kStage = kRows * kRowB;                 // bytes per stage
+    constexpr int kDma = kRows / 16 / 4;                  // direct loads per wave per stage (16 rows each)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    // blockIdx -> (row tile, vocabulary tile): consecutive workgroups of one XCD walk the row tiles of one vocabulary tile
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int bn = (slot / tiles_m) * 8 + xcd, bm = slot % tiles_m;
+    if (bn >= tiles_n) return;
+    const int m0 = bm * BM, n0 = bn * kBigBN;
+
+    // direct-load role: instruction j of this wave fills LDS rows 16*(4j + wave) .. +15 of the stage
+    // (rows 0..BM-1 = hidden, BM.. = W); lane -> (row = lane/4, position = lane%4),
+    // source chunk = position ^ swizzle(row), swizzle = 2*bit1(row) + bit2(row)
+    const uint16_t* src[kDma];
+#pragma unroll
+    for (int j = 0; j < kDma; ++j) {
+        const int row = 16 * (4 * j + wave) + (lane >> 2);
+        const int ch = (lane & 3) ^ (((row >> 1) & 1) * 2 + ((row >> 2) & 1));
+        // rows past M or V read the last valid row: their results are never stored
+        src[j] = row < BM ? A + (size_t)min(m0 + row, M - 1) * H + ch * 8
+                          : W + (size_t)min(n0 + row - BM, V - 1) * H + ch * 8;
+    }
+    auto issue = [&](int k0, unsigned char* stage) {
+#pragma unroll
+        for (int j = 0; j < kDma; ++j) lds_dma16(src[j] + k0, stage + 16 * (4 * j + wave) * kRowB);
+    };
+
+    f32x16 acc[TMW][4];
+#pragma unroll
+    for (int i = 0; i < TMW; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int r32 = lane & 31, kg = lane >> 5;
+    const int swz = ((r32 >> 1) & 1) * 2 + ((r32 >> 2) & 1);
+    const int nslab = H / kBigBK;                         // >= kBigStages (H >= 128)
+#pragma unroll
+    for (int s = 0; s < kBigStages - 1; ++s) issue(s * kBigBK, smem + s * kStage);
+    for (int s = 0; s < nslab; ++s) {
+        unsigned char* cur = smem + (s % kBigStages) * kStage;
+        // all but the two youngest slabs of this wave's loads have landed (the tail has fewer in flight)
+        if (s + 2 < nslab) __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * kDma) & 15) | (((2 * kDma) >> 4) << 14));
+        else if (s + 1 < nslab) __builtin_amdgcn_s_waitcnt(0x0F70 | (kDma & 15) | ((kDma >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();                                  // everyone's part of slab s is in LDS, slab s-1 is consumed
+        if (s + kBigStages - 1 < nslab) issue((s + kBigStages - 1) * kBigBK, smem + ((s + kBigStages - 1) % kBigStages) * kStage);
+        const unsigned char* sa = cur + (wm * (BM / 2) + r32) * kRowB;
+        const unsigned char* sb = cur + (BM + wn * 128 + r32) * kRowB;
+        bf16x8 fa[2][TMW], fb[2][4];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int off = ((ks * 2 + kg) ^ swz) << 4;
+#pragma unroll
+            for (int i = 0; i < TMW; ++i) fa[ks][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * kRowB + off);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) fb[ks][j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * kRowB + off);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int i = 0; i < TMW; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
+    }
+    // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
+#pragma unroll
+    for (int i = 0; i < TMW; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gc = n0 + wn * 128 + j * 32 + r32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int gr = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+                if (gr < M && gc < V) C[(size_t)gr * V + gc] = acc[i][j][r];
+            }
+        }
+}
+
+template <int TMW>
+static int launch_big(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
+{
+    constexpr int BM = 64 * TMW;
+    const size_t smem = (size_t)kBigStages * (BM + kBigBN) * kBigBK * 2;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_big_kernel<TMW>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
+        configured = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (V + kBigBN - 1) / kBigBN;
+    const long grid = (long)((tiles_n + 7) / 8) * 8 * tiles_m;
+    hipLaunchKernelGGL(lm_head_big_kernel<TMW>, dim3((unsigned)grid), dim3(256), smem, s, a, w, c, M, H, V, tiles_m, tiles_n);
+    return SPEC_OK;
+}
+
 static int device_cu_count()
 {
     static int cus = 0;
@@ -319,6 +442,11 @@ extern "C" int spec_lm_head(const void* hidden, const void* W, float* logits, in
         else if (M <= 96) rc = launch_skinny<6>(a, w, logits, M, H, V, s);
         else if (M <= 128) rc = launch_skinny<8>(a, w, logits, M, H, V, s);
         else rc = launch_skinny<10>(a, w, logits, M, H, V, s);
+        if (rc != SPEC_OK) return rc;
+    } else if (M > 160 && H % kBigBK == 0 && H >= kBigBK * kBigStages) {
+        // row tiles of 192 or 256: whichever wastes fewer padded rows
+        const int waste192 = (M + 191) / 192 * 192 - M, waste256 = (M + 255) / 256 * 256 - M;
+        const int rc = waste192 <= waste256 ? launch_big<3>(a, w, logits, M, H, V, s) : launch_big<4>(a, w, logits, M, H, V, s);
         if (rc != SPEC_OK) return rc;
     } else if (M <= 64) {
         const long tiles = (long)((M + 63) / 64) * ((V + 127) / 128);

@@ -33,15 +33,6 @@ constexpr float kMaxSlack = 6.0f;            // how far a step's maximum may exc
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
-// Written as inline assembly so that the compiler does not order it against later LDS reads by draining
-// the whole load queue: the kernel double-buffers and waits with explicit s_waitcnt vmcnt(n) instead.
-__device__ inline void lds_dma16(const void* g, void* lds_base)
-{
-    const uint32_t m0v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_base;
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0v) : "memory");
-}
-
 // Transposing LDS read.  In every group of 16 lanes, lane r supplies the address of 4 consecutive
 // 16-bit elements M[r][0..3]; lane j receives M[j/4][j%4], M[4 + j/4][j%4], M[8 + j/4][j%4], M[12 + j/4][j%4].
 __device__ inline s16x4 lds_read_tr(const void* lds)
