@@ -121,64 +121,86 @@ __device__ inline void load_strided(const float* __restrict__ row, int v0, int v
 }
 
 // ---- 1. per-segment statistics ---------------------------------------------------------------
+constexpr int kSegPerWg = 1;        // consecutive segments one workgroup handles (all loads issued up front)
+
 __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
     const float* __restrict__ logits, const float* __restrict__ temperature,
     const int32_t* __restrict__ qo_indptr, int B, int V, int nseg, bool vec,
     AcceptWorkspace w, int32_t* __restrict__ stats)
 {
-    __shared__ float s_m[kThreads / 64];
-    __shared__ int s_a[kThreads / 64];
-    __shared__ int s_bad[kThreads / 64];
-    __shared__ double s_z[kThreads / 64];
-    const int seg = blockIdx.x, row = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (stats && seg == 0 && row == 0 && tid < 4) stats[tid] = (tid == 2) ? B : 0;
+    __shared__ float s_m[kSegPerWg][kThreads / 64];
+    __shared__ int s_a[kSegPerWg][kThreads / 64];
+    __shared__ int s_bad[kSegPerWg][kThreads / 64];
+    __shared__ double s_z[kSegPerWg][kThreads / 64];
+    const int seg0 = blockIdx.x * kSegPerWg, row = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (stats && blockIdx.x == 0 && row == 0 && tid < 4) stats[tid] = (tid == 2) ? B : 0;
     const float* lrow = logits + (size_t)row * V;
-    const int v0 = seg * kSeg, vend = min(V, v0 + kSeg);
-    float x[kPerThread];
-    load_strided(lrow, v0, vend, vec, tid, x);
-
-    float m = -INFINITY;
-    int arg = 0x7FFFFFFF, bad = 0;
+    float x[kSegPerWg][kPerThread];
 #pragma unroll
-    for (int it = 0; it < kPerThread / 4; ++it)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const float xv = x[it * 4 + k];
-            bad |= (xv != xv);
-            if (xv > m) { m = xv; arg = v0 + (it * kThreads + tid) * 4 + k; }
-        }
-    wave_max_arg(m, arg);
-    bad = __any(bad);
-    if (lane == 0) { s_m[wave] = m; s_a[wave] = arg; s_bad[wave] = bad; }
-    __syncthreads();
-    float bm = s_m[0];
-    int ba = s_a[0], bb = s_bad[0];
-#pragma unroll
-    for (int k = 1; k < kThreads / 64; ++k) {
-        if (s_m[k] > bm || (s_m[k] == bm && s_a[k] < ba)) { bm = s_m[k]; ba = s_a[k]; }
-        bb |= s_bad[k];
+    for (int q = 0; q < kSegPerWg; ++q) {
+        const int v0 = (seg0 + q) * kSeg;
+        load_strided(lrow, min(v0, V), min(V, v0 + kSeg), vec, tid, x[q]);      // past the row: all -inf
     }
     const float T = temperature[find_request(qo_indptr, B, row)];
-    double z = 0.0;
-    if (T > 0.0f && !bb && bm > -INFINITY && bm < INFINITY) {
-        const double inv_t = 1.0 / (double)T, dm = (double)bm;
 #pragma unroll
-        for (int k = 0; k < kPerThread; ++k) z += exp(((double)x[k] - dm) * inv_t);
-        z = wave_sum(z);
-        if (lane == 0) s_z[wave] = z;
-        __syncthreads();
-        z = 0.0;
+    for (int q = 0; q < kSegPerWg; ++q) {
+        const int v0 = (seg0 + q) * kSeg;
+        float m = -INFINITY;
+        int arg = 0x7FFFFFFF, bad = 0;
 #pragma unroll
-        for (int k = 0; k < kThreads / 64; ++k) z += s_z[k];
+        for (int it = 0; it < kPerThread / 4; ++it)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float xv = x[q][it * 4 + k];
+                bad |= (xv != xv);
+                if (xv > m) { m = xv; arg = v0 + (it * kThreads + tid) * 4 + k; }
+            }
+        wave_max_arg(m, arg);
+        bad = __any(bad);
+        if (lane == 0) { s_m[q][wave] = m; s_a[q][wave] = arg; s_bad[q][wave] = bad; }
     }
-    if (tid == 0) {
-        const size_t o = (size_t)row * nseg + seg;
-        w.seg_max[o] = bm; w.seg_arg[o] = ba; w.seg_bad[o] = bb; w.seg_z[o] = z;
+    __syncthreads();
+    float bm[kSegPerWg];
+    int ba[kSegPerWg], bb[kSegPerWg];
+#pragma unroll
+    for (int q = 0; q < kSegPerWg; ++q) {
+        bm[q] = s_m[q][0]; ba[q] = s_a[q][0]; bb[q] = s_bad[q][0];
+#pragma unroll
+        for (int k = 1; k < kThreads / 64; ++k) {
+            if (s_m[q][k] > bm[q] || (s_m[q][k] == bm[q] && s_a[q][k] < ba[q])) { bm[q] = s_m[q][k]; ba[q] = s_a[q][k]; }
+            bb[q] |= s_bad[q][k];
+        }
+    }
+    if (T > 0.0f) {
+        const double inv_t = 1.0 / (double)T;
+#pragma unroll
+        for (int q = 0; q < kSegPerWg; ++q) {
+            double z = 0.0;
+            if (!bb[q] && bm[q] > -INFINITY && bm[q] < INFINITY) {
+                const double dm = (double)bm[q];
+#pragma unroll
+                for (int k = 0; k < kPerThread; ++k) z += exp(((double)x[q][k] - dm) * inv_t);
+            }
+            z = wave_sum(z);
+            if (lane == 0) s_z[q][wave] = z;
+        }
+        __syncthreads();
+    }
+    if (tid < kSegPerWg && seg0 + tid < nseg) {
+        double z = 0.0;
+        if (T > 0.0f)
+            for (int k = 0; k < kThreads / 64; ++k) z += s_z[tid][k];
+        // pick this thread's segment out of the register arrays without dynamic indexing
+        float fm = bm[0]; int fa = ba[0], fb = bb[0];
+#pragma unroll
+        for (int q = 1; q < kSegPerWg; ++q) if (tid == q) { fm = bm[q]; fa = ba[q]; fb = bb[q]; }
+        const size_t o = (size_t)row * nseg + seg0 + tid;
+        w.seg_max[o] = fm; w.seg_arg[o] = fa; w.seg_bad[o] = fb; w.seg_z[o] = z;
     }
 }
 
 // ---- 2. per-request decision -----------------------------------------------------------------
-__global__ __launch_bounds__(64) void accept_decide_kernel(
+__global__ __launch_bounds__(256) void accept_decide_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ tokens, const float* __restrict__ draft_probs,
     const float* __restrict__ temperature, const uint64_t* __restrict__ seeds, uint32_t round,
     const int32_t* __restrict__ qo_indptr, int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens,
@@ -187,18 +209,18 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
 {
     __shared__ double s_m[kMaxRows], s_z[kMaxRows];
     __shared__ int s_arg[kMaxRows], s_bad[kMaxRows];
-    const int i = blockIdx.x, lane = threadIdx.x;
+    const int i = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tid = threadIdx.x;
     const int r0 = qo_indptr[i], gamma = qo_indptr[i + 1] - r0 - 1;
     int32_t* emit = out_tokens + (size_t)i * (gamma_max + 1);
-    for (int j = lane; j <= gamma_max; j += 64) emit[j] = -1;
-    if (lane == 0) { w.job_row[i] = -1; accept_len[i] = 0; if (rollback) rollback[i] = 0; }
+    for (int j = tid; j <= gamma_max; j += 256) emit[j] = -1;
+    if (tid == 0) { w.job_row[i] = -1; accept_len[i] = 0; if (rollback) rollback[i] = 0; }
     if (gamma < 0 || gamma > gamma_max || r0 < 0 || r0 + gamma + 1 > M) {
-        if (lane == 0 && status_flags) atomicOr(status_flags, SPEC_FLAG_BAD_LENGTH);
+        if (tid == 0 && status_flags) atomicOr(status_flags, SPEC_FLAG_BAD_LENGTH);
         return;
     }
     const float T = temperature[i];
     const double Td = (double)T;
-    for (int j = 0; j <= gamma; ++j) {
+    for (int j = wave; j <= gamma; j += 4) {               // rows are merged by the four waves in parallel
         const size_t base = (size_t)(r0 + j) * nseg;
         float m = -INFINITY;
         int arg = 0x7FFFFFFF, bad = 0;
@@ -221,7 +243,7 @@ __global__ __launch_bounds__(64) void accept_decide_kernel(
         if (lane == 0) { s_m[j] = (double)m; s_z[j] = z; s_arg[j] = arg; s_bad[j] = bad; }
     }
     __syncthreads();
-    if (lane != 0) return;
+    if (tid != 0) return;
 
     int flags = 0;
     bool valid = (T >= 0.0f);
@@ -458,9 +480,9 @@ extern "C" int spec_accept(const float* logits, const int32_t* tokens, const flo
     carve(&w, (char*)workspace, B, M, nseg);
     const bool vec = (V % 4 == 0) && aligned(logits, 16) && (!draft_probs || aligned(draft_probs, 16));
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(accept_row_stats_kernel, dim3(nseg, M), dim3(kThreads), 0, s, logits, temperature, qo_indptr, B,
+    hipLaunchKernelGGL(accept_row_stats_kernel, dim3((nseg + kSegPerWg - 1) / kSegPerWg, M), dim3(kThreads), 0, s, logits, temperature, qo_indptr, B,
                        V, nseg, vec, w, stats);
-    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(64), 0, s, logits, tokens, draft_probs, temperature, seeds,
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(256), 0, s, logits, tokens, draft_probs, temperature, seeds,
                        round, qo_indptr, accept_len, out_tokens, rollback, stats, M, V, nseg, gamma_max, w, status_flags);
     if (seeds) {   // seeds == NULL promises an all-greedy batch: nothing is ever drawn
         hipLaunchKernelGGL(accept_residual_sums_kernel, dim3(nseg, B), dim3(kThreads), 0, s, logits, draft_probs, V,
