@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--config", default="mid", help="workload name in paper_2605_08151_amd.workloads.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-chunk", type=int, default=0, help="override keys per kv split (0 = library heuristic)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy 3 times (untimed): under rocprofv3 --pmc its FETCH_SIZE / "
+                         "WRITE_SIZE readings calibrate the counters against a known byte count")
     return ap.parse_args()
 
 
@@ -95,6 +98,13 @@ def main():
         step.commit(pt, sl, qo, fl, fc, cfg.P)
         if events: events[4].record()
 
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for k in range(args.warmup):
         run(k)
     torch.cuda.synchronize()
@@ -157,8 +167,10 @@ def main():
     print(json.dumps(out))
 
 
-def cpu_baseline(cfg, b, step, tokens, draft_probs, seeds, emitted_per_step):
-    """Times the oracle on a slice of the batch sized for ~10-30 s and extrapolates linearly per stage."""
+def cpu_baseline(cfg, b, step, tokens, draft_probs, seeds, emitted_per_step, budget_s=8.0):
+    """Times the oracle as it stands on this machine's host cores.  Each stage first runs on a small probe, then on
+    the largest slice of the real workload that the probe says fits ~budget_s seconds (the whole stage if it
+    fits), and is extrapolated linearly to full size."""
     import numpy as np
     import oracle
     from paper_2605_08151_amd import workloads as wl
@@ -167,38 +179,53 @@ def cpu_baseline(cfg, b, step, tokens, draft_probs, seeds, emitted_per_step):
     threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or os.cpu_count()
     B, M, V = b["B"], b["M"], cfg.V
     qo = b["qo_indptr"].cpu().numpy()
-    # attention: first n_seq requests (all heads, all rows)
-    n_seq = min(B, 4)
-    rows = int(qo[n_seq])
+    ctx, gam = b["ctx"].numpy().astype(np.int64), b["gammas"].numpy().astype(np.int64)
     kbits, vbits = wl.bf16_bits(b["k_cache"]), wl.bf16_bits(b["v_cache"])
-    t = time.perf_counter()
-    oracle.verify_attn(wl.bf16_bits(b["q"][:rows]), kbits, vbits, b["page_table"][:n_seq].cpu().numpy(),
-                       b["ctx"][:n_seq].numpy().astype(np.int32), qo[:n_seq + 1].copy(), b["scale"])
-    t_attn_sample = time.perf_counter() - t
-    w_all = float(((b["ctx"] + b["gammas"] + 1) * (b["gammas"] + 1)).sum())
-    w_s = float(((b["ctx"][:n_seq] + b["gammas"][:n_seq] + 1) * (b["gammas"][:n_seq] + 1)).sum())
-    t_attn = t_attn_sample * w_all / w_s
-    # LM head: all rows against the first v_s vocabulary entries
-    v_s = min(V, max(256, int(6.0e10 / (2.0 * M * cfg.H))))
-    t = time.perf_counter()
-    oracle.lm_head(wl.bf16_bits(b["hidden"]), wl.bf16_bits(b["W"][:v_s]))
-    t_lm = (time.perf_counter() - t) * V / v_s
-    # acceptance and commit: whole batch, on the GPU's logits
+    qbits = wl.bf16_bits(b["q"])
+    pt = b["page_table"].cpu().numpy()
+    work = (ctx + gam + 1) * (gam + 1)                      # key-row products per request
+
+    def attn_on(n_seq):
+        rows = int(qo[n_seq])
+        t = time.perf_counter()
+        oracle.verify_attn(qbits[:rows], kbits, vbits, pt[:n_seq].copy(), ctx[:n_seq].astype(np.int32),
+                           qo[:n_seq + 1].copy(), b["scale"])
+        return time.perf_counter() - t
+
+    n_probe = min(B, 2)
+    t_probe = attn_on(n_probe)
+    per_work = t_probe / float(work[:n_probe].sum())
+    n_seq = int(np.searchsorted(np.cumsum(work) * per_work, budget_s)) + 1
+    n_seq = max(n_probe, min(B, n_seq))
+    t_attn_sample = attn_on(n_seq) if n_seq > n_probe else t_probe
+    t_attn = t_attn_sample * float(work.sum()) / float(work[:n_seq].sum())
+
+    hbits = wl.bf16_bits(b["hidden"])
+    def lm_on(v_s):
+        t = time.perf_counter()
+        oracle.lm_head(hbits, wl.bf16_bits(b["W"][:v_s]))
+        return time.perf_counter() - t
+    v_probe = min(V, 2048)
+    t_probe = lm_on(v_probe)
+    v_s = max(v_probe, min(V, int(v_probe * budget_s / max(t_probe, 1e-6))))
+    t_lm_sample = lm_on(v_s) if v_s > v_probe else t_probe
+    t_lm = t_lm_sample * V / v_s
+
     gl = step.logits.cpu().numpy()
     dp = None if draft_probs is None else draft_probs.cpu().numpy()
     sd = None if seeds is None else seeds.cpu().numpy().view(np.uint64)
     t = time.perf_counter()
     ref = oracle.accept(gl, tokens.cpu().numpy(), dp, b["temperature"].cpu().numpy(), sd, 0, qo, b["gamma_max"])
     t_acc = time.perf_counter() - t
-    pt, sl = b["page_table"].cpu().numpy().copy(), b["ctx"].numpy().astype(np.int32).copy()
+    ptc, sl = pt.copy(), ctx.astype(np.int32).copy()
     fl, fc = b["free_list"].cpu().numpy().copy(), b["free_count"].cpu().numpy().copy()
     t = time.perf_counter()
-    oracle.kv_commit(pt, sl, qo, ref["accept_len"], fl, fc, cfg.P)
+    oracle.kv_commit(ptc, sl, qo, ref["accept_len"], fl, fc, cfg.P)
     t_commit = time.perf_counter() - t
     total = t_attn + t_lm + t_acc + t_commit
     return {"value": emitted_per_step / total, "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": f"attention on the first {n_seq} of {B} requests ({t_attn_sample:.2f} s, scaled by key*row count), "
-                      f"LM head on all {M} rows x first {v_s} of {V} vocabulary rows (scaled by V), "
+                      f"LM head on all {M} rows x the first {v_s} of {V} vocabulary rows ({t_lm_sample:.2f} s, scaled by V), "
                       f"acceptance and commit on the whole batch; stage seconds at full size: "
                       f"attn {t_attn:.2f}, lm_head {t_lm:.2f}, accept {t_acc:.3f}, commit {t_commit:.4f}"}
 

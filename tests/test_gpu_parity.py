@@ -370,3 +370,77 @@ def test_whole_step_small_hybrid_mix(sv, oracle):
     b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=True)
     _close(out.float().cpu().numpy(), ref_attn, "hybrid attn", sharp=True)
     _close(gl, oracle.lm_head(wl.bf16_bits(b["hidden"]), wl.bf16_bits(b["W"])), "hybrid logits")
+
+
+# --------------------------------------------------------------------------- BASELINE configurations at full size
+def _sampled_logits_check(oracle, b, gl, n_cols=192, seed=0):
+    """LM head at full size: the oracle recomputes all rows for a random sample of vocabulary entries
+    (plus the first and last 32, which sit in the ragged tiles)."""
+    V = b["W"].shape[0]
+    rng = np.random.default_rng(seed)
+    cols = np.unique(np.concatenate([rng.integers(0, V, n_cols), np.arange(32), np.arange(V - 32, V)]))
+    ref = oracle.lm_head(wl.bf16_bits(b["hidden"]), wl.bf16_bits(b["W"][torch.from_numpy(cols).cuda()]))
+    _close(gl[:, cols], ref, "sampled logits")
+
+
+@pytest.mark.parametrize("name", ["mid", "stochastic", "long"])
+def test_full_size_configuration(sv, oracle, name):
+    """BASELINE configurations 2, 3 and 4 at full size, in the launch configuration bench.py times:
+    attention against the oracle on every row, logits on sampled vocabulary entries, acceptance and
+    commit bit-exact on the GPU's own logits."""
+    cfg = wl.CONFIGS[name]
+    stochastic = cfg.temperature != ("const", 0.0)
+    b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=stochastic)
+    _close(out.float().cpu().numpy(), ref_attn, f"{name} attn")
+    _sampled_logits_check(oracle, b, gl)
+
+
+def test_full_size_hybrid_mix_properties(sv, oracle):
+    """BASELINE configuration 5 (B=256, gamma in {0,2,4,8}, lognormal contexts up to 32k, half sampled):
+    attention is checked on a sample of requests the oracle recomputes (all their rows and heads),
+    acceptance and commit are bit-exact on the whole batch."""
+    cfg = wl.CONFIGS["hybrid"]
+    b = wl.make_batch(cfg, device="cuda")
+    step = _step(b, cfg)
+    out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
+    torch.cuda.synchronize()
+    qo = b["qo_indptr"].cpu().numpy()
+    ctx = b["ctx"].numpy()
+    order = np.argsort(ctx)
+    pick = np.unique(np.concatenate([order[:3], order[-2:], np.random.default_rng(0).integers(0, cfg.B, 8)]))
+    rows = np.concatenate([np.arange(qo[i], qo[i + 1]) for i in pick])
+    sub_qo = np.zeros(len(pick) + 1, np.int32)
+    sub_qo[1:] = np.cumsum([qo[i + 1] - qo[i] for i in pick])
+    ref = oracle.verify_attn(wl.bf16_bits(b["q"][torch.from_numpy(rows).cuda()]), wl.bf16_bits(b["k_cache"]),
+                             wl.bf16_bits(b["v_cache"]), b["page_table"].cpu().numpy()[pick].copy(),
+                             b["seq_lens"].cpu().numpy()[pick].copy(), sub_qo, b["scale"])
+    _close(out.float().cpu().numpy()[rows], ref, "hybrid attn sample")
+    assert int(step.status.cpu()) == 0
+    del ref, out
+    # acceptance + commit on the whole batch
+    logits = step.lm_head(b["hidden"], b["W"])
+    torch.cuda.synchronize()
+    gl = logits.cpu().numpy()
+    _sampled_logits_check(oracle, b, gl, n_cols=64)
+    temp = b["temperature"].cpu().numpy()
+    tokens_g, _ = wl.draft_tokens_greedy(cfg, b["qo_indptr"], torch.from_numpy(gl.argmax(1)))
+    dp, tokens_s = wl.draft_probs_noisy(cfg, b["qo_indptr"], logits)
+    per_row_T = np.repeat(temp, np.diff(qo))
+    tokens = torch.where(torch.from_numpy(per_row_T > 0), tokens_s, tokens_g)
+    step.accept(tokens.cuda(), dp, b["temperature"], b["seeds"], 2, b["qo_indptr"])
+    torch.cuda.synchronize()
+    ref = oracle.accept(gl, tokens.numpy(), dp.cpu().numpy(), temp, b["seeds"].cpu().numpy().view(np.uint64), 2, qo,
+                        b["gamma_max"])
+    assert np.array_equal(step.accept_len.cpu().numpy(), ref["accept_len"])
+    assert np.array_equal(step.out_tokens.cpu().numpy(), ref["out_tokens"])
+    assert np.array_equal(step.rollback.cpu().numpy(), ref["rollback"])
+    # gamma = 0 requests (the padded parallel-mode candidates) emit exactly one token and never roll back
+    g0 = b["gammas"].numpy() == 0
+    assert (ref["accept_len"][g0] == 0).all() and (ref["rollback"][g0] == 0).all() and (ref["out_tokens"][g0, 0] >= 0).all()
+    pt, sl = b["page_table"].cpu().numpy().copy(), b["seq_lens"].cpu().numpy().copy()
+    fl, fc = b["free_list"].cpu().numpy().copy(), b["free_count"].cpu().numpy().copy()
+    oracle.kv_commit(pt, sl, qo, ref["accept_len"], fl, fc, cfg.P)
+    step.commit(b["page_table"], b["seq_lens"], b["qo_indptr"], b["free_list"], b["free_count"], cfg.P)
+    torch.cuda.synchronize()
+    assert np.array_equal(b["page_table"].cpu().numpy(), pt) and np.array_equal(b["seq_lens"].cpu().numpy(), sl)
+    assert np.array_equal(b["free_list"].cpu().numpy()[:int(fc[0])], fl[:int(fc[0])])
