@@ -120,25 +120,29 @@ __global__ __launch_bounds__(256) void lm_head_tiled_kernel(
 //   * C^T tiles come out with 4 consecutive vocabulary entries per lane: 16-byte stores along V.
 // ------------------------------------------------------------------------------------------------
 constexpr int kSlab = 128;                   // k per hidden slab in LDS
-constexpr int kRingSlabs = 4;                // W register ring: 4 slabs = 16 chunks of 32 k = 512 k ahead
-constexpr int kRing = 4 * kRingSlabs;
 constexpr int kHPitch = kSlab * 2 + 16;      // bytes per hidden row in LDS (272: 16 rows -> 16 bank groups)
-constexpr int kPassCols = 128;               // vocabulary entries per workgroup pass (4 waves x 32)
+constexpr int kPassCols = 128;               // vocabulary entries per workgroup pass (4 wave columns x 32)
 
-template <int TM, int TN>
+// TM: 16-row tiles of hidden in total; TN: 16-entry tiles of W per wave; MS: wave rows (the 4*MS waves form a
+// 4 x MS grid: wave column = 32 vocabulary entries, wave row = TM/MS row tiles; with MS = 2 two waves share
+// every SIMD and hide each other's load latency); RS: depth of the W register ring in 128-k slabs.
+template <int TM, int TN, int MS, int RS>
 __device__ inline void skinny_pass(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
-                                   int M, int H, int V, int wave_c0, int wave_nc, bool vec_store,
+                                   int M, int H, int V, int wave_c0, int wave_nc, int mh, bool vec_store,
                                    unsigned char* smem, int tid)
 {
-    constexpr int BM = TM * 16;
-    constexpr int H_LOADS = BM * 16 / 256;            // 16-byte chunks of a hidden slab per thread (= TM)
+    constexpr int kThreads = 256 * MS;
+    constexpr int TMH = (TM + MS - 1) / MS;           // row tiles per wave
+    constexpr int BM = TMH * MS * 16;                 // hidden rows staged in LDS (rows >= M repeat row M-1)
+    constexpr int H_LOADS = (BM * 16 + kThreads - 1) / kThreads;   // 16-byte chunks of a hidden slab per thread
+    constexpr int kRing = 4 * RS;
     const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
 
-    f32x4 acc[TN][TM];
+    f32x4 acc[TN][TMH];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int tm = 0; tm < TMH; ++tm) acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const uint16_t* wptr[TN];
 #pragma unroll
@@ -158,19 +162,19 @@ __device__ inline void skinny_pass(const uint16_t* __restrict__ A, const uint16_
 #pragma unroll
         for (int p = 0; p < H_LOADS; ++p) {
             // rows past M read row M-1: every output row depends on its own hidden row only
-            const int idx = tid + p * 256, row = min(idx >> 4, M - 1), ch = idx & 15;
+            const int idx = min(tid + p * kThreads, BM * 16 - 1), row = min(idx >> 4, M - 1), ch = idx & 15;
             hreg[set][p] = *reinterpret_cast<const u32x4*>(A + (size_t)row * H + k0 + ch * 8);
         }
     };
     auto stash_h = [&](int set, unsigned char* buf) {
 #pragma unroll
         for (int p = 0; p < H_LOADS; ++p) {
-            const int idx = tid + p * 256, row = idx >> 4, ch = idx & 15;
+            const int idx = min(tid + p * kThreads, BM * 16 - 1), row = idx >> 4, ch = idx & 15;
             *reinterpret_cast<u32x4*>(buf + row * kHPitch + ch * 16) = hreg[set][p];
         }
     };
 
-    const int nslab = H / kSlab;                       // multiple of kRingSlabs
+    const int nslab = H / kSlab;                       // multiple of RS
     unsigned char* buf0 = smem;
     unsigned char* buf1 = smem + BM * kHPitch;
     __syncthreads();                                  // previous pass is done with both buffers
@@ -184,51 +188,52 @@ __device__ inline void skinny_pass(const uint16_t* __restrict__ A, const uint16_
     for (int c = 4; c < kRing; ++c) fetch_w(c, (c >> 2) * kSlab);
     stash_h(0, buf0);
     __syncthreads();
-    for (int s4 = 0; s4 < nslab; s4 += kRingSlabs) {
+    const int hrow0 = mh * TMH * 16 + l16;
+    for (int sR = 0; sR < nslab; sR += RS) {
 #pragma unroll
-        for (int par = 0; par < kRingSlabs; ++par) {
-            const int s = s4 + par;
-            unsigned char* cur = (par & 1) ? buf1 : buf0;
-            unsigned char* nxt = (par & 1) ? buf0 : buf1;   // last read in slab s-1, before the barrier that ended it
+        for (int par = 0; par < RS; ++par) {
+            const int s = sR + par;
+            unsigned char* cur = (s & 1) ? buf1 : buf0;
+            unsigned char* nxt = (s & 1) ? buf0 : buf1;   // last read in slab s-1, before the barrier that ended it
             // past the end the prefetches wrap to a valid slab (L2 hits, results unused): no branch in the loop
             const int kh = min((s + 2) * kSlab, H - kSlab);
-            const int kw = min((s + kRingSlabs) * kSlab, H - kSlab);
-            fetch_h(par & 1, kh);
+            const int kw = min((s + RS) * kSlab, H - kSlab);
+            fetch_h(s & 1, kh);
             // The scheduler must not move the loads: their program order is what the in-order wait
             // counters are derived from (see above), so every step is fenced.
             __builtin_amdgcn_sched_barrier(0);
-            bf16x8 hf[2][TM];
+            bf16x8 hf[2][TMH];
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                hf[0][tm] = *reinterpret_cast<const bf16x8*>(cur + (tm * 16 + l16) * kHPitch + kg * 16);
+            for (int tm = 0; tm < TMH; ++tm)
+                hf[0][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + kg * 16);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if (c < 3) {
 #pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
-                        hf[(c + 1) & 1][tm] = *reinterpret_cast<const bf16x8*>(cur + (tm * 16 + l16) * kHPitch + (c + 1) * 64 + kg * 16);
+                    for (int tm = 0; tm < TMH; ++tm)
+                        hf[(c + 1) & 1][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + (c + 1) * 64 + kg * 16);
                 }
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) {
                     const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[tn][par * 4 + c]);
 #pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
+                    for (int tm = 0; tm < TMH; ++tm)
                         acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, hf[c & 1][tm], acc[tn][tm], 0, 0, 0);
                 }
                 fetch_w(par * 4 + c, kw);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            stash_h((par & 1) ^ 1, nxt);              // slab s+1, requested one slab ago
+            stash_h((s & 1) ^ 1, nxt);                // slab s+1, requested one slab ago
             __syncthreads();
         }
     }
-    // acc[tn][tm][i] = C[row 16tm + l16][entry wave_c0 + 16tn + 4kg + i]
+    // acc[tn][tm][i] = C[row hrow0 + 16tm][entry wave_c0 + 16tn + 4kg + i]
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         const int e = tn * 16 + kg * 4;
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) {
-            const int row = tm * 16 + l16;
+        for (int tm = 0; tm < TMH; ++tm) {
+            const int row = hrow0 + tm * 16;
             if (row < M && e < wave_nc) {
                 float* dst = C + (size_t)row * V + wave_c0 + e;
                 if (vec_store && e + 3 < wave_nc) {
@@ -243,24 +248,25 @@ __device__ inline void skinny_pass(const uint16_t* __restrict__ A, const uint16_
     }
 }
 
-template <int TM>
-__global__ __launch_bounds__(256, 1) void lm_head_skinny_kernel(
+template <int TM, int MS, int RS>
+__global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
     int M, int H, int V, int cols_per_wg, bool vec_store)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wcol = wave & 3, mh = wave >> 2;
     const int c_begin = blockIdx.x * cols_per_wg;
     const int c_end = min(V, c_begin + cols_per_wg);
     for (int pass0 = c_begin; pass0 < c_end; pass0 += kPassCols) {
         const int pass_cols = min(kPassCols, c_end - pass0);
         const int per_wave = pass_cols == kPassCols ? kPassCols / 4 : (((pass_cols + 3) / 4 + 3) & ~3);
-        const int wave_c0 = pass0 + wave * per_wave;
-        int wave_nc = pass_cols - wave * per_wave;
+        const int wave_c0 = pass0 + wcol * per_wave;
+        int wave_nc = pass_cols - wcol * per_wave;
         wave_nc = wave_nc < 0 ? 0 : (wave_nc > per_wave ? per_wave : wave_nc);
-        if (per_wave > 16) skinny_pass<TM, 2>(A, W, C, M, H, V, wave_c0, wave_nc, vec_store, smem, tid);
-        else skinny_pass<TM, 1>(A, W, C, M, H, V, wave_c0, wave_nc, vec_store, smem, tid);
+        if (per_wave > 16) skinny_pass<TM, 2, MS, RS>(A, W, C, M, H, V, wave_c0, wave_nc, mh, vec_store, smem, tid);
+        else skinny_pass<TM, 1, MS, RS>(A, W, C, M, H, V, wave_c0, wave_nc, mh, vec_store, smem, tid);
     }
 }
 
@@ -387,6 +393,9 @@ static int launch_big(const uint16_t* a, const uint16_t* w, float* c, int M, int
     return SPEC_OK;
 }
 
+int g_lm_kernel = 0;   // benchmark hook: 0 = automatic, 1 = weight-streaming, 2 = MFMA-bound, 3 = plain tiled,
+                       // 4 = weight-streaming with 8 waves (4 x 2) and a 2-slab ring
+
 static int device_cu_count()
 {
     static int cus = 0;
@@ -401,13 +410,14 @@ static int device_cu_count()
     return cus;
 }
 
-template <int TM>
+template <int TM, int MS, int RS>
 static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
 {
-    const size_t smem = 2 * (size_t)TM * 16 * kHPitch;
+    constexpr int BM = (TM + MS - 1) / MS * MS * 16;
+    const size_t smem = 2 * (size_t)BM * kHPitch;
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM, MS, RS>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
         configured = true;
@@ -417,8 +427,17 @@ static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, 
     if (cols < 64) cols = 64;
     const int grid = (V + cols - 1) / cols;
     const bool vec_store = (V % 4 == 0);
-    hipLaunchKernelGGL(lm_head_skinny_kernel<TM>, dim3(grid), dim3(256), smem, s, a, w, c, M, H, V, cols, vec_store);
+    hipLaunchKernelGGL((lm_head_skinny_kernel<TM, MS, RS>), dim3(grid), dim3(256 * MS), smem, s, a, w, c, M, H, V, cols, vec_store);
     return SPEC_OK;
+}
+
+template <int TM>
+static int launch_skinny_auto(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
+{
+    // measured on MI355X at M = 160, V = 151936: 4 waves with a 4-slab ring ~375-400 us, 8 waves (two wave
+    // rows re-reading the same W rows) with a 2-slab ring ~500 us
+    if (g_lm_kernel == 4) return launch_skinny<TM, 2, 2>(a, w, c, M, H, V, s);
+    return launch_skinny<TM, 1, 4>(a, w, c, M, H, V, s);
 }
 
 }  // namespace specv
@@ -435,15 +454,16 @@ extern "C" int spec_lm_head(const void* hidden, const void* W, float* logits, in
     hipStream_t s = (hipStream_t)stream;
     const uint16_t* a = (const uint16_t*)hidden;
     const uint16_t* w = (const uint16_t*)W;
-    if (M <= 160 && H % (kRingSlabs * kSlab) == 0) {
+    const int force = g_lm_kernel;
+    if ((force == 0 || force == 1 || force == 4) && M <= 160 && H % (4 * kSlab) == 0) {
         int rc;
-        if (M <= 32) rc = launch_skinny<2>(a, w, logits, M, H, V, s);
-        else if (M <= 64) rc = launch_skinny<4>(a, w, logits, M, H, V, s);
-        else if (M <= 96) rc = launch_skinny<6>(a, w, logits, M, H, V, s);
-        else if (M <= 128) rc = launch_skinny<8>(a, w, logits, M, H, V, s);
-        else rc = launch_skinny<10>(a, w, logits, M, H, V, s);
+        if (M <= 32) rc = launch_skinny_auto<2>(a, w, logits, M, H, V, s);
+        else if (M <= 64) rc = launch_skinny_auto<4>(a, w, logits, M, H, V, s);
+        else if (M <= 96) rc = launch_skinny_auto<6>(a, w, logits, M, H, V, s);
+        else if (M <= 128) rc = launch_skinny_auto<8>(a, w, logits, M, H, V, s);
+        else rc = launch_skinny_auto<10>(a, w, logits, M, H, V, s);
         if (rc != SPEC_OK) return rc;
-    } else if (M > 160 && H % kBigBK == 0 && H >= kBigBK * kBigStages) {
+    } else if ((force == 2 || (force == 0 && M > 160)) && H % kBigBK == 0 && H >= kBigBK * kBigStages) {
         // row tiles of 192 or 256: whichever wastes fewer padded rows
         const int waste192 = (M + 191) / 192 * 192 - M, waste256 = (M + 255) / 256 * 256 - M;
         const int rc = waste192 <= waste256 ? launch_big<3>(a, w, logits, M, H, V, s) : launch_big<4>(a, w, logits, M, H, V, s);
