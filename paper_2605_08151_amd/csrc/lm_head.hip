@@ -114,29 +114,42 @@ __global__ __launch_bounds__(256) void lm_head_tiled_kernel(
 //   * Each wave reads ITS vocabulary rows straight from HBM into registers in MFMA operand order
 //     (v_mfma_f32_16x16x32_bf16, W on the A side: lane (entry l%16, k-group l/16) takes 16 B at
 //     k = 32c + 8*(l/16), so the four lanes of a row cover 64 contiguous bytes per instruction).
-//     The registers form a ring of 512 k: a chunk is re-requested 512 k ahead right after the MFMAs
-//     that consumed it.  No W byte touches LDS.
+//     The registers form a ring of 256 k that is refilled 256 k ahead, two chunks (the two halves of a
+//     128-byte line) at a time, right after the MFMAs that consumed them.  No W byte touches LDS.
+//     Measured with the math removed, a deeper ring does not stream faster: the rate is set by the
+//     number of open rows and by the traffic through the CU's vector L1, not by the bytes in flight.
 //   * hidden (all M rows, L2-resident) is staged through LDS in 128-wide k slabs shared by the waves.
+//     Its L2 hits are not free: per pass every CU pulls all of hidden (1.25x the W bytes of the pass at
+//     M = 160) through the same L1 port, and the time this takes adds to the W stream (measured:
+//     +50 us on a 225 us stream), so the pass is as wide as the open-row limit above allows.
 //   * C^T tiles come out with 4 consecutive vocabulary entries per lane: 16-byte stores along V.
 // ------------------------------------------------------------------------------------------------
 constexpr int kSlab = 128;                   // k per hidden slab in LDS
 constexpr int kHPitch = kSlab * 2 + 16;      // bytes per hidden row in LDS (272: 16 rows -> 16 bank groups)
 constexpr int kPassCols = 128;               // vocabulary entries per workgroup pass (4 wave columns x 32)
 
-// TM: 16-row tiles of hidden in total; TN: 16-entry tiles of W per wave; MS: wave rows (the 4*MS waves form a
-// 4 x MS grid: wave column = 32 vocabulary entries, wave row = TM/MS row tiles; with MS = 2 two waves share
-// every SIMD and hide each other's load latency); RS: depth of the W register ring in 128-k slabs.
-template <int TM, int TN, int MS, int RS>
-__device__ inline void skinny_pass(const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
-                                   int M, int H, int V, int wave_c0, int wave_nc, int mh, bool vec_store,
-                                   unsigned char* smem, int tid)
+// TM: 16-row tiles of hidden in total; MS: wave rows (the 4*MS waves form a 4 x MS grid: wave column = 32
+// vocabulary entries, wave row = TM/MS row tiles; with MS = 2 two waves share every SIMD and hide each other's
+// load latency); RS: depth of the W register ring in 128-k slabs; PAIR: refill two chunks at a time.
+template <int TM, int MS, int RS, int PAIR>
+__global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
+    int M, int H, int V, int cols_per_wg, bool vec_store)
 {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int TN = 2;                             // 16-entry tiles of W per wave
     constexpr int kThreads = 256 * MS;
     constexpr int TMH = (TM + MS - 1) / MS;           // row tiles per wave
     constexpr int BM = TMH * MS * 16;                 // hidden rows staged in LDS (rows >= M repeat row M-1)
     constexpr int H_LOADS = (BM * 16 + kThreads - 1) / kThreads;   // 16-byte chunks of a hidden slab per thread
     constexpr int kRing = 4 * RS;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wcol = wave & 3, mh = wave >> 2;
     const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
+    const int c_begin = blockIdx.x * cols_per_wg;
+    const int c_end = min(V, c_begin + cols_per_wg);
+    if (c_begin >= c_end) return;
 
     f32x4 acc[TN][TMH];
 #pragma unroll
@@ -144,16 +157,24 @@ __device__ inline void skinny_pass(const uint16_t* __restrict__ A, const uint16_
 #pragma unroll
         for (int tm = 0; tm < TMH; ++tm) acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const uint16_t* wptr[TN];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        // entries past the wave's range read a valid row instead (branch-free loop); their results are never stored
-        wptr[tn] = W + (size_t)min(wave_c0 + tn * 16 + l16, V - 1) * H + kg * 8;
-    }
     // Loads retire in order, so waiting for a young hidden load would drain the whole W ring.  The
     // hidden slab s+2 is therefore requested at the start of slab s and only stashed at the end of slab
     // s+1, when every load older than it is one the math needed anyway.
+    const uint16_t* wptr[TN];
     u32x4 wreg[TN][kRing], hreg[2][H_LOADS];
+    int wave_c0 = 0, wave_nc = 0;
+    auto open_pass = [&](int pass0) {                 // the wave's share of a pass and its W row pointers
+        const int pass_cols = min(kPassCols, c_end - pass0);
+        const int per_wave = pass_cols == kPassCols ? kPassCols / 4 : (((pass_cols + 3) / 4 + 3) & ~3);
+        wave_c0 = pass0 + wcol * per_wave;
+        wave_nc = max(0, min(per_wave, pass_cols - wcol * per_wave));
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            // entries past the wave's range re-read its last row (branch-free loop); their results are never stored
+            const int e = max(0, min(tn * 16 + l16, wave_nc - 1));
+            wptr[tn] = W + (size_t)min(wave_c0 + e, V - 1) * H + kg * 8;
+        }
+    };
     auto fetch_w = [&](int c, int k0) {               // chunk c of the ring <- k0 + 32*(c%4) .. +32
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) wreg[tn][c] = *reinterpret_cast<const u32x4*>(wptr[tn] + k0 + (c & 3) * 32);
@@ -173,100 +194,102 @@ __device__ inline void skinny_pass(const uint16_t* __restrict__ A, const uint16_
             *reinterpret_cast<u32x4*>(buf + row * kHPitch + ch * 16) = hreg[set][p];
         }
     };
+    // First requests of a pass, in the order of the steady state (hidden slab, then W chunks), so that the
+    // wait counts the compiler derives for the loop entry are not tighter than those of the back edge.
+    auto open_loads = [&]() {
+        fetch_h(0, 0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) fetch_w(c, 0);
+        fetch_h(1, kSlab);                            // slab 1, stashed at the end of slab 0
+#pragma unroll
+        for (int c = 4; c < kRing; ++c) fetch_w(c, (c >> 2) * kSlab);
+    };
 
-    const int nslab = H / kSlab;                       // multiple of RS
+    const int nslab = H / kSlab;                      // multiple of RS
     unsigned char* buf0 = smem;
     unsigned char* buf1 = smem + BM * kHPitch;
-    __syncthreads();                                  // previous pass is done with both buffers
-    // Prologue in the order of the steady state (hidden slab, then W chunks), so that the wait counts the
-    // compiler derives for the loop entry are not tighter than those of the back edge.
-    fetch_h(0, 0);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) fetch_w(c, 0);
-    fetch_h(1, kSlab);                                // slab 1, stashed at the end of slab 0
-#pragma unroll
-    for (int c = 4; c < kRing; ++c) fetch_w(c, (c >> 2) * kSlab);
-    stash_h(0, buf0);
-    __syncthreads();
     const int hrow0 = mh * TMH * 16 + l16;
-    for (int sR = 0; sR < nslab; sR += RS) {
+    int pass0 = c_begin;
+    open_pass(pass0);
+    open_loads();
+    for (;;) {
+        stash_h(0, buf0);                             // every wave left the previous pass through a barrier
+        __syncthreads();
+        for (int sR = 0; sR < nslab; sR += RS) {
 #pragma unroll
-        for (int par = 0; par < RS; ++par) {
-            const int s = sR + par;
-            unsigned char* cur = (s & 1) ? buf1 : buf0;
-            unsigned char* nxt = (s & 1) ? buf0 : buf1;   // last read in slab s-1, before the barrier that ended it
-            // past the end the prefetches wrap to a valid slab (L2 hits, results unused): no branch in the loop
-            const int kh = min((s + 2) * kSlab, H - kSlab);
-            const int kw = min((s + RS) * kSlab, H - kSlab);
-            fetch_h(s & 1, kh);
-            // The scheduler must not move the loads: their program order is what the in-order wait
-            // counters are derived from (see above), so every step is fenced.
-            __builtin_amdgcn_sched_barrier(0);
-            bf16x8 hf[2][TMH];
-#pragma unroll
-            for (int tm = 0; tm < TMH; ++tm)
-                hf[0][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + kg * 16);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (c < 3) {
-#pragma unroll
-                    for (int tm = 0; tm < TMH; ++tm)
-                        hf[(c + 1) & 1][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + (c + 1) * 64 + kg * 16);
-                }
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[tn][par * 4 + c]);
-#pragma unroll
-                    for (int tm = 0; tm < TMH; ++tm)
-                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, hf[c & 1][tm], acc[tn][tm], 0, 0, 0);
-                }
-                fetch_w(par * 4 + c, kw);
+            for (int par = 0; par < RS; ++par) {
+                const int s = sR + par;
+                unsigned char* cur = (s & 1) ? buf1 : buf0;
+                unsigned char* nxt = (s & 1) ? buf0 : buf1;   // last read in slab s-1, before the barrier that ended it
+                // past the end the prefetches wrap to a valid slab (L2 hits, results unused): no branch in the loop
+                const int kh = min((s + 2) * kSlab, H - kSlab);
+                const int kw = min((s + RS) * kSlab, H - kSlab);
+                fetch_h(s & 1, kh);
+                // The scheduler must not move the loads: their program order is what the in-order wait
+                // counters are derived from (see above), so every step is fenced.
                 __builtin_amdgcn_sched_barrier(0);
-            }
-            stash_h((s & 1) ^ 1, nxt);                // slab s+1, requested one slab ago
-            __syncthreads();
-        }
-    }
-    // acc[tn][tm][i] = C[row hrow0 + 16tm][entry wave_c0 + 16tn + 4kg + i]
+                bf16x8 hf[2][TMH];
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        const int e = tn * 16 + kg * 4;
+                for (int tm = 0; tm < TMH; ++tm)
+                    hf[0][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + kg * 16);
 #pragma unroll
-        for (int tm = 0; tm < TMH; ++tm) {
-            const int row = hrow0 + tm * 16;
-            if (row < M && e < wave_nc) {
-                float* dst = C + (size_t)row * V + wave_c0 + e;
-                if (vec_store && e + 3 < wave_nc) {
-                    *reinterpret_cast<f32x4*>(dst) = acc[tn][tm];
-                } else {
+                for (int c = 0; c < 4; ++c) {
+                    if (c < 3) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (e + i < wave_nc) dst[i] = acc[tn][tm][i];
+                        for (int tm = 0; tm < TMH; ++tm)
+                            hf[(c + 1) & 1][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + (c + 1) * 64 + kg * 16);
+                    }
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[tn][par * 4 + c]);
+#pragma unroll
+                        for (int tm = 0; tm < TMH; ++tm)
+                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, hf[c & 1][tm], acc[tn][tm], 0, 0, 0);
+                    }
+                    if (!PAIR) {
+                        fetch_w(par * 4 + c, kw);
+                    } else if (c & 1) {
+                        fetch_w(par * 4 + c - 1, kw);
+                        fetch_w(par * 4 + c, kw);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                stash_h((s & 1) ^ 1, nxt);            // slab s+1, requested one slab ago
+                __syncthreads();
             }
         }
-    }
-}
-
-template <int TM, int MS, int RS>
-__global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
-    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
-    int M, int H, int V, int cols_per_wg, bool vec_store)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wcol = wave & 3, mh = wave >> 2;
-    const int c_begin = blockIdx.x * cols_per_wg;
-    const int c_end = min(V, c_begin + cols_per_wg);
-    for (int pass0 = c_begin; pass0 < c_end; pass0 += kPassCols) {
-        const int pass_cols = min(kPassCols, c_end - pass0);
-        const int per_wave = pass_cols == kPassCols ? kPassCols / 4 : (((pass_cols + 3) / 4 + 3) & ~3);
-        const int wave_c0 = pass0 + wcol * per_wave;
-        int wave_nc = pass_cols - wcol * per_wave;
-        wave_nc = wave_nc < 0 ? 0 : (wave_nc > per_wave ? per_wave : wave_nc);
-        if (per_wave > 16) skinny_pass<TM, 2, MS, RS>(A, W, C, M, H, V, wave_c0, wave_nc, mh, vec_store, smem, tid);
-        else skinny_pass<TM, 1, MS, RS>(A, W, C, M, H, V, wave_c0, wave_nc, mh, vec_store, smem, tid);
+        // Stores and loads share the in-order queue: a wave that stored its tile first would have to see
+        // those writes land before the first W chunk of the next pass counts as arrived.  So the next
+        // pass is opened first and the finished tile is stored behind its loads.
+        const int st_c0 = wave_c0, st_nc = wave_nc;
+        pass0 += kPassCols;
+        const bool more = pass0 < c_end;
+        if (more) {
+            open_pass(pass0);
+            open_loads();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // acc[tn][tm][i] = C[row hrow0 + 16tm][entry st_c0 + 16tn + 4kg + i]
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int e = tn * 16 + kg * 4;
+#pragma unroll
+            for (int tm = 0; tm < TMH; ++tm) {
+                const int row = hrow0 + tm * 16;
+                if (row < M && e < st_nc) {
+                    float* dst = C + (size_t)row * V + st_c0 + e;
+                    if (vec_store && e + 3 < st_nc) {
+                        *reinterpret_cast<f32x4*>(dst) = acc[tn][tm];
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (e + i < st_nc) dst[i] = acc[tn][tm][i];
+                    }
+                }
+                acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        if (!more) break;
     }
 }
 
@@ -394,7 +417,8 @@ static int launch_big(const uint16_t* a, const uint16_t* w, float* c, int M, int
 }
 
 int g_lm_kernel = 0;   // benchmark hook: 0 = automatic, 1 = weight-streaming, 2 = MFMA-bound, 3 = plain tiled,
-                       // 4 = weight-streaming with 8 waves (4 x 2) and a 2-slab ring
+                       // 4 = weight-streaming with 8 waves (4 x 2) and a 2-slab ring, 5/6/7 = 4 waves with
+                       // 2-slab ring / 4-slab ring + paired refills / 2-slab ring + paired refills (the default)
 
 static int device_cu_count()
 {
@@ -410,14 +434,14 @@ static int device_cu_count()
     return cus;
 }
 
-template <int TM, int MS, int RS>
+template <int TM, int MS, int RS, int PAIR = 0>
 static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
 {
     constexpr int BM = (TM + MS - 1) / MS * MS * 16;
     const size_t smem = 2 * (size_t)BM * kHPitch;
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM, MS, RS>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM, MS, RS, PAIR>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
         configured = true;
@@ -427,17 +451,21 @@ static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, 
     if (cols < 64) cols = 64;
     const int grid = (V + cols - 1) / cols;
     const bool vec_store = (V % 4 == 0);
-    hipLaunchKernelGGL((lm_head_skinny_kernel<TM, MS, RS>), dim3(grid), dim3(256 * MS), smem, s, a, w, c, M, H, V, cols, vec_store);
+    hipLaunchKernelGGL((lm_head_skinny_kernel<TM, MS, RS, PAIR>), dim3(grid), dim3(256 * MS), smem, s, a, w, c, M, H, V, cols, vec_store);
     return SPEC_OK;
 }
 
 template <int TM>
 static int launch_skinny_auto(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
 {
-    // measured on MI355X at M = 160, V = 151936: 4 waves with a 4-slab ring ~375-400 us, 8 waves (two wave
-    // rows re-reading the same W rows) with a 2-slab ring ~500 us
+    // measured on MI355X at M = 160, V = 151936 inside the whole verify step: 4 waves with a 2-slab ring and
+    // paired refills ~347 us, with a 4-slab ring and single refills ~363 us, 8 waves (two wave rows re-reading
+    // the same W rows) with a 2-slab ring ~470 us
     if (g_lm_kernel == 4) return launch_skinny<TM, 2, 2>(a, w, c, M, H, V, s);
-    return launch_skinny<TM, 1, 4>(a, w, c, M, H, V, s);
+    if (g_lm_kernel == 5) return launch_skinny<TM, 1, 2>(a, w, c, M, H, V, s);
+    if (g_lm_kernel == 6) return launch_skinny<TM, 1, 4, 1>(a, w, c, M, H, V, s);
+    if (g_lm_kernel == 7) return launch_skinny<TM, 1, 2, 1>(a, w, c, M, H, V, s);
+    return launch_skinny<TM, 1, 2, 1>(a, w, c, M, H, V, s);
 }
 
 }  // namespace specv
@@ -455,7 +483,7 @@ extern "C" int spec_lm_head(const void* hidden, const void* W, float* logits, in
     const uint16_t* a = (const uint16_t*)hidden;
     const uint16_t* w = (const uint16_t*)W;
     const int force = g_lm_kernel;
-    if ((force == 0 || force == 1 || force == 4) && M <= 160 && H % (4 * kSlab) == 0) {
+    if ((force == 0 || force == 1 || force >= 4) && M <= 160 && H % (4 * kSlab) == 0) {
         int rc;
         if (M <= 32) rc = launch_skinny_auto<2>(a, w, logits, M, H, V, s);
         else if (M <= 64) rc = launch_skinny_auto<4>(a, w, logits, M, H, V, s);
