@@ -64,8 +64,12 @@ const char* spec_last_error_string(void);
 /* Library version, major * 1000 + minor. host. */
 int spec_version(void);
 
-/* Benchmark hook (host): overrides a launch heuristic; never changes results beyond fp32 summation
- * order.  key "attn_chunk": keys per kv split of spec_verify_attn, 0 = automatic. */
+/* Benchmark hook (host, process-wide): overrides a launch heuristic; never changes results beyond fp32
+ * summation order.  Keys: "attn_chunk" = keys per kv split of spec_verify_attn, 0 = automatic;
+ * "lm_kernel" = kernel used by spec_lm_head, 0 = automatic (weight-streaming kernel for M <= 160, MFMA-bound
+ * kernel above), 1 = weight-streaming, 2 = MFMA-bound, 3 = plain tiled, 4..7 = weight-streaming variants
+ * (wave count / register-ring depth).  A forced kernel that cannot take the shape falls back to the plain
+ * tiled one.  Unknown key: SPEC_EINVAL. */
 int spec_set_tuning(const char* key, int value);
 
 /* ---------------------------------------------------------------------------
@@ -88,7 +92,7 @@ int spec_set_tuning(const char* key, int value);
  *                                                natural-log sum-exp of the scaled scores
  * Host bounds the launch is sized from: max_kv_len >= max_i(c_i + n_i),
  * max_q_len >= max_i n_i.  Built for D = 128, page_size = 16, Hq % Hkv == 0,
- * Hq / Hkv <= 64; anything else is SPEC_ESHAPE.  fp32 accumulation.
+ * (Hq / Hkv) * max_q_len <= 128 query rows per kv head; anything else is SPEC_ESHAPE.  fp32 accumulation.
  * Requests that break a bound are skipped (rows left untouched) and flagged.
  * ------------------------------------------------------------------------- */
 size_t spec_verify_attn_workspace_bytes(int B, int M, int Hq, int Hkv, int D, int max_kv_len, int max_q_len);

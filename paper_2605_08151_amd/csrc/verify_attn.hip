@@ -3,9 +3,10 @@
 // parallel-mode candidates, i.e. ordinary decode).
 //
 // Work decomposition (HBM-bound: 512 bytes of K+V per key per kv head, 8..72 flop per byte):
-//   grid = (kv split, kv head, request).  A workgroup of 4 waves streams one contiguous chunk of one
-//   request's keys for one kv head; wave w owns keys 32w..32w+31 of every 128-key step and all
-//   G * n_i query rows (query heads of the group x candidate positions).  A wave copies ITS two pages
+//   grid = (kv split, kv head, request).  A workgroup of NW waves (8 when the query block is at most 32
+//   rows, else 4) streams one contiguous chunk of one request's keys for one kv head; wave w owns keys
+//   32w..32w+31 of every 32*NW-key step and all G * n_i query rows (query heads of the group x
+//   candidate positions).  A wave copies ITS two pages
 //   (K and V, 4 KB each, contiguous in HBM) straight into its private 16 KB of LDS with direct
 //   global->LDS loads (no staging registers), so the waves of a workgroup never wait for each other
 //   inside the loop; latency is hidden by the other waves resident on the SIMD.
@@ -53,7 +54,7 @@ struct AttnParams {
     float* part_m;      // [M*Hq, splits]   running max, log2 domain
     float* part_l;      // [M*Hq, splits]
     int32_t* status_flags;
-    int max_pages, num_pages, Hq, Hkv, G, M, max_kv_len, max_q_len, chunk_target, splits, dbg;
+    int max_pages, num_pages, Hq, Hkv, G, M, max_kv_len, max_q_len, chunk_target, splits;
     float scale_log2e;
 };
 
@@ -111,7 +112,6 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
     // range read page 0 instead, so the wait counts below are constants) ----
     const int drow = lane >> 4, dpos = lane & 15;        // direct-load role: row within a group of 4, 16-byte position
     auto issue_step = [&](int wbase, unsigned char* buf) {
-        if (p.dbg & 1) return;
 #pragma unroll
         for (int pg = 0; pg < 2; ++pg) {
             const int t0 = wbase + pg * kP;
@@ -191,7 +191,6 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
             }
         }
 
-        if (p.dbg & 2) continue;
         // ---- S^T = K Q^T for the wave's two 16-key blocks ----
         bf16x8 kf[2][4];
 #pragma unroll
@@ -417,7 +416,6 @@ __global__ __launch_bounds__(256) void verify_attn_combine_kernel(AttnParams p, 
 }
 
 int g_attn_chunk_override = 0;
-int g_attn_dbg = 0;
 
 static int attn_cu_count()
 {
@@ -539,7 +537,7 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
     p.page_table = page_table; p.seq_lens = seq_lens; p.qo_indptr = qo_indptr;
     p.status_flags = status_flags;
     p.max_pages = max_pages_per_seq; p.num_pages = num_pages; p.Hq = Hq; p.Hkv = Hkv; p.G = G;
-    p.dbg = g_attn_dbg; p.M = M; p.max_kv_len = max_kv_len; p.max_q_len = max_q_len;
+    p.M = M; p.max_kv_len = max_kv_len; p.max_q_len = max_q_len;
     p.chunk_target = attn_chunk_target(B, Hkv, max_kv_len, attn_waves(NR) * 32);
     p.out = (uint16_t*)out; p.lse = lse;
     p.splits = (max_kv_len + p.chunk_target - 1) / p.chunk_target;
