@@ -271,11 +271,11 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
         }
         // acc[tn][tm][i] = C[row hrow0 + 16tm][entry st_c0 + 16tn + 4kg + i]
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            const int e = tn * 16 + kg * 4;
+        for (int tm = 0; tm < TMH; ++tm) {
+            const int row = hrow0 + tm * 16;
 #pragma unroll
-            for (int tm = 0; tm < TMH; ++tm) {
-                const int row = hrow0 + tm * 16;
+            for (int tn = 0; tn < TN; ++tn) {     // the two 64-byte halves of a row's 128 bytes back to back
+                const int e = tn * 16 + kg * 4;
                 if (row < M && e < st_nc) {
                     float* dst = C + (size_t)row * V + st_c0 + e;
                     if (vec_store && e + 3 < st_nc) {
@@ -301,6 +301,10 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
 //     (no staging registers): three slabs are in flight while one is multiplied, one barrier per slab.
 //     Rows are 64 B in LDS with the 16-byte chunks XOR-swizzled by row pair, so the 8 lanes that read
 //     8 consecutive rows at the same k hit 8 different bank groups.
+//     Measured with the math removed: the direct loads deliver ~12.5 TB/s into the CUs of the chip whatever
+//     the slab width or ring depth (a 256 x 256 tile needs 16 TB/s at the MFMA peak); staging through
+//     registers instead (17.5 TB/s at 128 B per row) gave the same kernel time, because the time is set
+//     by the waves waiting for each other's operands at the per-slab barrier, not by either pipe alone.
 //   * Workgroup -> tile mapping keeps the row tiles of one vocabulary tile on the same XCD (workgroups
 //     are dealt round-robin to the 8 XCDs), so a W slab is fetched into one L2 only.
 // ------------------------------------------------------------------------------------------------
@@ -384,15 +388,17 @@ __global__ __launch_bounds__(256, 1) void lm_head_big_kernel(
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
     }
-    // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
+    // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.  The four
+    // vocabulary tiles of a row are stored back to back, so that a row's 512 contiguous bytes reach the
+    // memory system together (measured: the epilogue costs ~100 us instead of ~290 at M = 1024).
 #pragma unroll
     for (int i = 0; i < TMW; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int gc = n0 + wn * 128 + j * 32 + r32;
+        for (int r = 0; r < 16; ++r) {
+            const int gr = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int gr = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+            for (int j = 0; j < 4; ++j) {
+                const int gc = n0 + wn * 128 + j * 32 + r32;
                 if (gr < M && gc < V) C[(size_t)gr * V + gc] = acc[i][j][r];
             }
         }
