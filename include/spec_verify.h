@@ -156,6 +156,28 @@ int spec_accept(const float* logits, const int32_t* tokens, const float* draft_p
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * spec_next_mode — execution mode of round n+1 (Method, "Rollback-Based Mode
+ * Selection", eq. mode_switch_batch) from the observed rollback ratio
+ * r_hat = |R_n| / B and the critical ratio (Section "Throughput-Guided Hybrid
+ * Coordination", eq. r_threshold)
+ *   r* = (gamma - 1) L t_draft / ((t_target + (gamma - 1) t_draft) (L - 1)),
+ * L = emitted tokens / B.  PARALLEL iff r_hat <= r*.  With L <= 1 (the
+ * derivation assumes L > 1) r* is +infinity: a round then yields one token
+ * per request in either mode and the ordinary round is the longer one.
+ *   stats_host: HOST copy of the stats[4] written by spec_accept.
+ *   gamma: speculative tokens per verification in the paper's counting, i.e.
+ *     candidate rows per request (drafts + the bonus position); t_draft,
+ *     t_target: latency of one draft step / one target verification, same unit.
+ *   r_hat, r_star: optional outputs (host).
+ * Pure host arithmetic; launches nothing.  Returns SPEC_MODE_PARALLEL or
+ * SPEC_MODE_ORDINARY, or SPEC_EINVAL (< 0) on NULL / inconsistent arguments.
+ * ------------------------------------------------------------------------- */
+#define SPEC_MODE_ORDINARY 0
+#define SPEC_MODE_PARALLEL 1
+int spec_next_mode(const int32_t* stats_host, double gamma, double t_draft, double t_target,
+                   double* r_hat, double* r_star);
+
+/* ---------------------------------------------------------------------------
  * spec_kv_commit — Commit(p_n, y_n, L_n) on the KV cache (Appendix "Target
  * side"; rollback frees the KV of the rejected suffix, Appendix "Draft side").
  *   new_len_i = c_i + a_i + 1; pages ceil(new_len_i / P) .. ceil((c_i + n_i) / P) - 1

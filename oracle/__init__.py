@@ -43,6 +43,8 @@ def _load():
         lib.oracle_thr_ordinary.argtypes = [ctypes.c_double] * 5
         lib.oracle_thr_parallel.argtypes = [ctypes.c_double] * 4
         lib.oracle_r_star.argtypes = [ctypes.c_double] * 4
+        lib.oracle_next_mode.restype = ctypes.c_int
+        lib.oracle_next_mode.argtypes = [ctypes.c_int] * 3 + [ctypes.c_double] * 3 + [ctypes.POINTER(ctypes.c_double)] * 2
         _lib = lib
     return _lib
 
@@ -144,3 +146,11 @@ def thr_parallel(B, L, r, T_T):
 
 def r_star(L, gamma, T_D, T_T):
     return float(_load().oracle_r_star(L, gamma, T_D, T_T))
+
+
+def next_mode(rollback_count, emitted, B, gamma, T_D, T_T):
+    """(mode, r_hat, r_star): mode 1 = PARALLEL, 0 = ORDINARY (Method, eq. mode_switch_batch)."""
+    rh, rs = ctypes.c_double(), ctypes.c_double()
+    mode = _load().oracle_next_mode(int(rollback_count), int(emitted), int(B), float(gamma), float(T_D), float(T_T),
+                                    ctypes.byref(rh), ctypes.byref(rs))
+    return int(mode), rh.value, rs.value

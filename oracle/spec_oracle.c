@@ -362,3 +362,18 @@ double oracle_r_star(double L, double gamma, double T_D, double T_T)
 {
     return (gamma - 1.0) * L * T_D / ((T_T + (gamma - 1.0) * T_D) * (L - 1.0));
 }
+
+/* Mode of round n+1 (Method, eq. mode_switch_batch): 1 = PARALLEL iff r_hat = |R_n| / B <= r*, else
+ * 0 = ORDINARY.  L is the mean number of tokens a request emitted in round n.  With L <= 1 the
+ * derivation's assumption L > 1 fails: speculation then yields one token per request either way, the
+ * ordinary round is longer by (gamma-1) T_D, so PARALLEL is never worse and is returned. */
+int oracle_next_mode(int rollback_count, int emitted, int B, double gamma, double T_D, double T_T,
+                     double* r_hat_out, double* r_star_out)
+{
+    double r_hat = (double)rollback_count / (double)B;
+    double L = (double)emitted / (double)B;
+    double rs = L > 1.0 ? oracle_r_star(L, gamma, T_D, T_T) : INFINITY;
+    if (r_hat_out) *r_hat_out = r_hat;
+    if (r_star_out) *r_star_out = rs;
+    return r_hat <= rs ? 1 : 0;
+}

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libspecverify.so")
 EXPORTS = (
     "spec_last_error_string", "spec_version", "spec_set_tuning",
     "spec_verify_attn_workspace_bytes", "spec_verify_attn", "spec_lm_head",
-    "spec_accept_workspace_bytes", "spec_accept", "spec_kv_commit",
+    "spec_accept_workspace_bytes", "spec_accept", "spec_kv_commit", "spec_next_mode",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -52,6 +52,9 @@ def _load():
     lib.spec_accept.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.spec_kv_commit.restype = i32
     lib.spec_kv_commit.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp]
+    lib.spec_next_mode.restype = i32
+    lib.spec_next_mode.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                   ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     return lib
 
 
@@ -78,6 +81,18 @@ def _check(rc):
 
 def spec_version():
     return _lib.spec_version()
+
+
+MODE_ORDINARY, MODE_PARALLEL = 0, 1
+
+
+def spec_next_mode(stats_host, gamma, t_draft, t_target):
+    """(mode, r_hat, r_star) from a host copy of spec_accept's stats[4]."""
+    arr = (ctypes.c_int32 * 4)(*[int(x) for x in stats_host])
+    rh, rs = ctypes.c_double(), ctypes.c_double()
+    mode = _lib.spec_next_mode(arr, float(gamma), float(t_draft), float(t_target), ctypes.byref(rh), ctypes.byref(rs))
+    _check(mode if mode < 0 else 0)
+    return int(mode), rh.value, rs.value
 
 
 def spec_set_tuning(key: str, value: int):

@@ -1,6 +1,7 @@
 // Library-wide pieces of the C ABI: error text, version, tuning hooks.
 #include "common.h"
 
+#include <cmath>
 #include <cstring>
 
 namespace specv {
@@ -28,4 +29,27 @@ extern "C" int spec_set_tuning(const char* key, int value)
     if (key && std::strcmp(key, "attn_chunk") == 0) { specv::g_attn_chunk_override = value; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_kernel") == 0) { specv::g_lm_kernel = value; return SPEC_OK; }
     return specv::fail(SPEC_EINVAL, "spec_set_tuning: unknown key '%s'", key ? key : "(null)");
+}
+
+// Mode of the next round from the counters spec_accept left in stats[4] (paper, Method, "Rollback-Based Mode
+// Selection", eq. mode_switch_batch; threshold: Section "Throughput-Guided Hybrid Coordination", eq. r_threshold).
+// Host arithmetic on four integers; nothing is launched.
+extern "C" int spec_next_mode(const int32_t* stats_host, double gamma, double t_draft, double t_target,
+                              double* r_hat, double* r_star)
+{
+    using namespace specv;
+    if (!stats_host) return fail(SPEC_EINVAL, "spec_next_mode: NULL stats");
+    const int rollbacks = stats_host[0], emitted = stats_host[1], B = stats_host[2];
+    if (B <= 0 || rollbacks < 0 || rollbacks > B || emitted < 0)
+        return fail(SPEC_EINVAL, "spec_next_mode: inconsistent stats (rollbacks=%d emitted=%d B=%d)", rollbacks, emitted, B);
+    if (!(gamma >= 1.0) || !(t_draft >= 0.0) || !(t_target > 0.0))
+        return fail(SPEC_EINVAL, "spec_next_mode: need gamma >= 1, t_draft >= 0, t_target > 0");
+    const double rh = (double)rollbacks / (double)B;
+    const double L = (double)emitted / (double)B;
+    // with L <= 1 a round yields one token per request in either mode and the ordinary round is the longer one
+    const double rs = L > 1.0 ? (gamma - 1.0) * L * t_draft / ((t_target + (gamma - 1.0) * t_draft) * (L - 1.0))
+                              : (double)INFINITY;
+    if (r_hat) *r_hat = rh;
+    if (r_star) *r_star = rs;
+    return rh <= rs ? SPEC_MODE_PARALLEL : SPEC_MODE_ORDINARY;
 }

@@ -219,6 +219,25 @@ def test_greedy_accept_is_bit_exact(sv, oracle, V):
     assert got["stats"][1] == int((ref["accept_len"] + 1).sum())
 
 
+@pytest.mark.parametrize("rho", [0.2, 0.6, 0.95])
+def test_mode_rule_from_device_counters(sv, oracle, rho):
+    # eq. mode_switch_batch: the counters spec_accept leaves on the device give the same mode, r_hat and r* as
+    # the oracle's rule applied to the oracle's own acceptance result
+    V = 4097
+    rng = np.random.default_rng(int(rho * 100))
+    gammas = np.full(48, 4)
+    qo = _qo(gammas)
+    logits = rng.normal(0, 0.03, (qo[-1], V)).astype(np.float32)
+    cfg = wl.VerifyConfig("g", V, len(gammas), (4,), ("const", 1), 8, 1, 64, V, rho=rho)
+    tokens, _ = wl.draft_tokens_greedy(cfg, torch.from_numpy(qo), torch.from_numpy(logits.argmax(1)))
+    got, ref = _accept_both(sv, oracle, logits, tokens.numpy(), None, np.zeros(len(gammas), np.float32), None, 0, qo, 4)
+    _assert_same(got, ref, gammas)
+    for (t_d, t_t) in [(1.0, 10.0), (3.0, 40.0), (0.2, 47.0)]:
+        want = oracle.next_mode(int(ref["rollback"].sum()), int((ref["accept_len"] + 1).sum()), len(gammas), 5, t_d, t_t)
+        have = sv.spec_next_mode(got["stats"], 5, t_d, t_t)
+        assert have[0] == want[0] and have[1] == want[1] and math.isclose(have[2], want[2], rel_tol=1e-15)
+
+
 def test_greedy_ties_and_duplicates_across_segments(sv, oracle):
     V = 10000
     logits = np.zeros((3, V), np.float32)
