@@ -54,6 +54,12 @@ struct AttnParams {
     float* part_m;      // [M*Hq, splits]   running max, log2 domain
     float* part_l;      // [M*Hq, splits]
     int32_t* status_flags;
+    // balanced work list written by verify_attn_plan_kernel (all null when requests are split by the fixed
+    // chunk_target instead): hdr = {items, keys per chunk}; req[i] = {splits of request i, first partial slot};
+    // items[k] = {request, split, splits of the request, first partial slot}
+    const int32_t* plan_hdr;
+    const int32_t* plan_req;
+    const int32_t* plan_items;
     int max_pages, num_pages, Hq, Hkv, G, M, max_kv_len, max_q_len, chunk_target, splits;
     float scale_log2e;
 };
@@ -76,22 +82,38 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
-    const int split = blockIdx.x, kvh = blockIdx.y, i = blockIdx.z;
+    const int kvh = blockIdx.y;
+    int split, i, ns_plan = 0, pb_plan = 0;
+    if (p.plan_items) {
+        // one workgroup per item of the balanced list; the grid is sized from a host bound
+        if ((int)blockIdx.x >= p.plan_hdr[0]) return;
+        const int* it = p.plan_items + 4 * (size_t)blockIdx.x;
+        i = __builtin_amdgcn_readfirstlane(it[0]);
+        split = __builtin_amdgcn_readfirstlane(it[1]);
+        ns_plan = __builtin_amdgcn_readfirstlane(it[2]);
+        pb_plan = __builtin_amdgcn_readfirstlane(it[3]);
+    } else {
+        split = blockIdx.x;
+        i = blockIdx.z;
+    }
     unsigned char* sKV = smem + wave * (NBUF * kWaveLds); // this wave's NBUF x (32 K rows, 32 V rows)
     unsigned char* sQ = smem + NW * NBUF * kWaveLds;      // shared: NR*16 query rows
     int32_t* sPT = reinterpret_cast<int32_t*>(sQ + NR * 16 * kRowBytes);   // shared: page ids of this chunk
 
     const int r0 = p.qo_indptr[i], n = p.qo_indptr[i + 1] - r0, c = p.seq_lens[i];
     if (!request_ok(r0, n, c, p)) {
-        if (split == 0 && kvh == 0 && tid == 0 && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_LENGTH);
+        if (!p.plan_items && split == 0 && kvh == 0 && tid == 0 && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_LENGTH);
         return;
     }
     const int len = c + n;
-    const int ns = (len + p.chunk_target - 1) / p.chunk_target;
+    const int ns = p.plan_items ? ns_plan : (len + p.chunk_target - 1) / p.chunk_target;
     if (split >= ns) return;
     const int chunk = (((len + ns - 1) / ns) + kP - 1) & ~(kP - 1);
     const int kbeg = split * chunk;
     const int kend = min(len, kbeg + chunk);
+    // partial slot of (candidate row j, head h, split): part_base + (j*Hq + h)*part_ns + split
+    const size_t part_base = p.plan_items ? (size_t)pb_plan : (size_t)r0 * p.Hq * p.splits;
+    const size_t part_ns = p.plan_items ? (size_t)ns : (size_t)p.splits;
     const int G = p.G, R = G * n;
     const int nrt = (R + 15) >> 4;                        // row tiles this request really has (wave-uniform, <= NR)
     const int32_t* pt = p.page_table + (size_t)i * p.max_pages;
@@ -340,7 +362,6 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
 #pragma unroll
     for (int rt = 0; rt < NR; ++rt) fscale[rt] = exp2f(m_run[rt] - s_mx[rt * 16 + l16]);
     // rows of this unit: r = j*G + gq  ->  global (row r0+j, head kvh*G+gq)
-    const size_t unit_stride = (size_t)p.splits;
 #pragma unroll
     for (int ds = 0; ds < 4; ++ds) {
 #pragma unroll
@@ -359,7 +380,7 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
             const int j = r / G, gq = r - j * G;
             const size_t rowhead = (size_t)(r0 + j) * p.Hq + kvh * G + gq;
             if (FINAL) p.out[rowhead * kD + ds * 32 + dl] = (uint16_t)f32_to_bf16_bits(sum / s_lt[r]);
-            else p.part_o[(rowhead * unit_stride + split) * kD + ds * 32 + dl] = sum;
+            else p.part_o[(part_base + ((size_t)j * p.Hq + kvh * G + gq) * part_ns + split) * kD + ds * 32 + dl] = sum;
         }
         __syncthreads();
     }
@@ -369,10 +390,116 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
         if (FINAL) {
             if (p.lse) p.lse[rowhead] = (s_mx[r] + log2f(s_lt[r])) * 0.6931471805599453f;
         } else {
-            p.part_m[rowhead * unit_stride + split] = s_mx[r];
-            p.part_l[rowhead * unit_stride + split] = s_lt[r];
+            const size_t slot = part_base + ((size_t)j * p.Hq + kvh * G + gq) * part_ns + split;
+            p.part_m[slot] = s_mx[r];
+            p.part_l[slot] = s_lt[r];
         }
     }
+}
+
+// Balanced work list for ragged batches (one workgroup, B <= 1024 requests).  The fixed chunk_target of the
+// host is sized for "every request as long as the bound"; when the real lengths are shorter or spread out,
+// the chip is under-filled or unbalanced.  Here the chunk length is derived from the real total instead:
+// the smallest c (a multiple of the workgroup step, min_chunk <= c <= max_chunk) with
+// sum_i ceil(len_i / c) <= target_items, request i is cut into ceil(len_i / c) equal chunks, and the items are
+// listed longest chunk first, so that workgroups dispatched in list order finish together.
+// Launched with B rounded up to whole waves as the workgroup size.
+__global__ __launch_bounds__(1024) void verify_attn_plan_kernel(AttnParams p, int B, int target_items, int step_keys,
+                                                                int min_chunk, int max_chunk, int max_items,
+                                                                int32_t* hdr, int32_t* req, int32_t* items)
+{
+    __shared__ __attribute__((aligned(16))) int s_key[1024];
+    __shared__ int s_ns[1024], s_rows[1024], s_req[1024];
+    __shared__ float s_redf[16];
+    __shared__ int s_redi[2][16];
+    __shared__ int s_scan_a[16], s_scan_b[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+    int len = 0, n = 0, bad = 0;
+    if (tid < B) {
+        const int r0 = p.qo_indptr[tid];
+        n = p.qo_indptr[tid + 1] - r0;
+        const int c = p.seq_lens[tid];
+        if (request_ok(r0, n, c, p)) len = c + n; else { bad = 1; n = 0; }
+    }
+    const int any_bad = __syncthreads_or(bad);
+    // Total keys, as an fp32 estimate: it only seeds the chunk length, the loop below counts items exactly.
+    float tf = (float)len;
+    for (int d = 32; d >= 1; d >>= 1) tf += __shfl_xor(tf, d, 64);
+    if (lane == 0) s_redf[wave] = tf;
+    __syncthreads();
+    float T = 0.0f;
+    for (int w = 0; w < nw; ++w) T += s_redf[w];
+    // chunk lengths are whole steps; the arithmetic is done in step units and in 32 bits / fp32 estimates
+    // (64-bit integer division is a long software routine on this hardware)
+    const int lo_steps = (min_chunk + step_keys - 1) / step_keys, hi_steps = max_chunk / step_keys;
+    auto clamp_steps = [&](float x) -> int {
+        int v = (int)ceilf(x);
+        return v < lo_steps ? lo_steps : (v > hi_steps ? hi_steps : v);
+    };
+    int cs = clamp_steps(T / ((float)target_items * (float)step_keys));
+    int c = cs * step_keys;
+#pragma unroll 1
+    for (int it = 0; it < 8; ++it) {
+        int cnt = len ? (len + c - 1) / c : 0;
+        for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d, 64);
+        if (lane == 0) s_redi[it & 1][wave] = cnt;        // two buffers: the next iteration writes the other one
+        __syncthreads();
+        int N = 0;
+        for (int w = 0; w < nw; ++w) N += s_redi[it & 1][w];
+        if (N <= target_items || cs >= hi_steps) break;
+        const int cs2 = clamp_steps((float)cs * (float)N / (float)target_items);
+        cs = cs2 > cs ? cs2 : cs + 1;
+        c = cs * step_keys;
+    }
+    const int ns = len ? (len + c - 1) / c : 0;
+    const int key = ns ? (len + ns - 1) / ns : 0;          // keys per chunk of this request
+    // position in the list: requests ordered by chunk length, longest first (ties: request order).  Chunk
+    // length (<= max_chunk < 2^21) and reversed request index are packed into one word, so that a position
+    // costs one comparison per other request; 64 words are fetched per round before any is used.
+    const uint32_t mine = ((uint32_t)key << 10) | (uint32_t)(1023 - tid);
+    s_key[tid] = tid < B ? (int)mine : 0;
+    __syncthreads();
+    int rank = 0;
+    if (tid < B) {
+        const int kmax = (int)blockDim.x;
+        for (int k0 = 0; k0 < kmax; k0 += 64) {
+            u32x4 v[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v[j] = *reinterpret_cast<const u32x4*>(&s_key[k0 + 4 * j]);
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                rank += (int)(v[j].x > mine) + (int)(v[j].y > mine) + (int)(v[j].z > mine) + (int)(v[j].w > mine);
+        }
+    }
+    __syncthreads();
+    if (tid < B) { s_ns[rank] = ns; s_rows[rank] = ns * n; s_req[rank] = tid; }
+    __syncthreads();
+    // exclusive prefix sums over the ordered requests: items before, partial rows before
+    int a = tid < B ? s_ns[tid] : 0, b = tid < B ? s_rows[tid] : 0;
+    int ia = a, ib = b;
+    for (int d = 1; d < 64; d <<= 1) {
+        const int ua = __shfl_up(ia, d, 64), ub = __shfl_up(ib, d, 64);
+        if (lane >= d) { ia += ua; ib += ub; }
+    }
+    if (lane == 63) { s_scan_a[wave] = ia; s_scan_b[wave] = ib; }
+    __syncthreads();
+    int base_a = 0, base_b = 0;
+    for (int w = 0; w < wave; ++w) { base_a += s_scan_a[w]; base_b += s_scan_b[w]; }
+    const int item0 = base_a + ia - a, row0 = base_b + ib - b;
+    if (tid < B) {
+        const int rq = s_req[tid];
+        const int pb = row0 * p.Hq;                      // first partial slot of the request
+        reinterpret_cast<u32x2*>(req)[rq] = u32x2{(uint32_t)a, (uint32_t)pb};
+        for (int sp = 0; sp < a; ++sp)
+            if (item0 + sp < max_items)
+                reinterpret_cast<u32x4*>(items)[item0 + sp] = u32x4{(uint32_t)rq, (uint32_t)sp, (uint32_t)a, (uint32_t)pb};
+    }
+    if (tid == (int)blockDim.x - 1) {
+        const int total = item0 + a;
+        hdr[0] = total < max_items ? total : max_items;
+        hdr[1] = c;
+    }
+    if (tid == 0 && any_bad && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_LENGTH);
 }
 
 // Merge the split partials of one (row, head) and write bf16 (and lse).  256 threads: lane group q = tid/32
@@ -392,8 +519,9 @@ __global__ __launch_bounds__(256) void verify_attn_combine_kernel(AttnParams p, 
     const int n = p.qo_indptr[i + 1] - p.qo_indptr[i], c = p.seq_lens[i];
     if (!request_ok(p.qo_indptr[i], n, c, p) || row >= p.qo_indptr[i + 1]) return;
     const int len = c + n;
-    const int ns = (len + p.chunk_target - 1) / p.chunk_target;
-    const size_t unit = ((size_t)row * p.Hq + hq) * p.splits;
+    const int ns = p.plan_req ? p.plan_req[2 * i] : (len + p.chunk_target - 1) / p.chunk_target;
+    const size_t unit = p.plan_req ? (size_t)p.plan_req[2 * i + 1] + ((size_t)(row - p.qo_indptr[i]) * p.Hq + hq) * ns
+                                   : ((size_t)row * p.Hq + hq) * p.splits;
     float mx = kNegBig;
     for (int s = 0; s < ns; ++s) mx = fmaxf(mx, p.part_m[unit + s]);
     f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -412,6 +540,42 @@ __global__ __launch_bounds__(256) void verify_attn_combine_kernel(AttnParams p, 
         for (int q = 0; q < 8; ++q) { a += s_num[q][tid]; dsum += s_den[q]; }
         p.out[((size_t)row * p.Hq + hq) * kD + tid] = (uint16_t)f32_to_bf16_bits(a / dsum);
         if (p.lse && tid == 0) p.lse[(size_t)row * p.Hq + hq] = (mx + log2f(dsum)) * 0.6931471805599453f;
+    }
+}
+
+// The same merge for requests cut into few pieces: one workgroup per candidate row, lane group q = tid/32 takes
+// heads q, q+8, ... and walks the splits of its (row, head) in order; 8x fewer, fuller workgroups than above.
+__global__ __launch_bounds__(256) void verify_attn_combine_rows_kernel(AttnParams p, int B)
+{
+    const int row = blockIdx.x, tid = threadIdx.x, grp = tid >> 5, d4 = (tid & 31) * 4;
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (p.qo_indptr[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    const int i = lo;
+    const int n = p.qo_indptr[i + 1] - p.qo_indptr[i], c = p.seq_lens[i];
+    if (!request_ok(p.qo_indptr[i], n, c, p) || row >= p.qo_indptr[i + 1]) return;
+    const int len = c + n;
+    const int ns = p.plan_req ? p.plan_req[2 * i] : (len + p.chunk_target - 1) / p.chunk_target;
+    for (int hq = grp; hq < p.Hq; hq += 8) {
+        const size_t unit = p.plan_req ? (size_t)p.plan_req[2 * i + 1] + ((size_t)(row - p.qo_indptr[i]) * p.Hq + hq) * ns
+                                       : ((size_t)row * p.Hq + hq) * p.splits;
+        float mx = kNegBig;
+        for (int s = 0; s < ns; ++s) mx = fmaxf(mx, p.part_m[unit + s]);
+        f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
+        float den = 0.0f;
+        for (int s = 0; s < ns; ++s) {
+            const float w = exp2f(p.part_m[unit + s] - mx);
+            num += w * *reinterpret_cast<const f32x4*>(p.part_o + (unit + s) * kD + d4);
+            den += w * p.part_l[unit + s];
+        }
+        const float inv = 1.0f / den;
+        u32x2 packed;
+        packed.x = pack_bf16x2(num.x * inv, num.y * inv);
+        packed.y = pack_bf16x2(num.z * inv, num.w * inv);
+        *reinterpret_cast<u32x2*>(p.out + ((size_t)row * p.Hq + hq) * kD + d4) = packed;
+        if (p.lse && (tid & 31) == 0) p.lse[(size_t)row * p.Hq + hq] = (mx + log2f(den)) * 0.6931471805599453f;
     }
 }
 
@@ -453,6 +617,45 @@ static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
 }
 
 static int attn_waves(int NR) { return NR <= 2 ? 8 : 4; }      // 8 waves need <= 256 registers per lane
+
+// Balanced work list (verify_attn_plan_kernel): used when requests are long enough for a few microseconds of
+// planning to pay, numerous enough for their length spread to matter, and the fixed chunk would split them anyway.
+int g_attn_plan = 0;          // benchmark hook: 0 = automatic, 1 = always (B <= 1024), 2 = never
+int g_attn_plan_waves = 0;    // benchmark hook: work items per CU the plan aims at, 0 = automatic
+constexpr int kPlanMinChunk = 512, kPlanMaxChunk = 8192;
+
+struct AttnPlanCfg {
+    bool on;
+    int target_items, max_items, step_keys;
+    size_t hdr_bytes, req_bytes, items_bytes, slots;
+};
+
+static AttnPlanCfg attn_plan_cfg(int B, int Hq, int Hkv, int max_kv_len, int max_q_len, int NR, int chunk_target)
+{
+    AttnPlanCfg c{};
+    c.step_keys = attn_waves(NR) * 32;
+    const bool splits_anyway = chunk_target < max_kv_len;
+    const long cus = attn_cu_count();
+    // Pays when many requests of unknown, possibly very different lengths share the chip (measured on MI355X,
+    // 256 requests of 256..32768 keys: 264 -> 213 us).  A few long requests are cut finely by the fixed chunk
+    // anyway and run at the memory system's rate either way (8 x 32k..64k: 52 us without, 57 with the list).
+    c.on = B <= 1024 && g_attn_plan != 2 &&
+           (g_attn_plan == 1 || (splits_anyway && max_kv_len >= 8192 && (long)B * Hkv * 4 >= cus));
+    // one workgroup is resident per CU (LDS): few requests are cut to exactly one round of equal items,
+    // many requests to about two rounds, which the longest-first order packs
+    const int per_cu = g_attn_plan_waves > 0 ? g_attn_plan_waves : ((long)B * Hkv * 2 <= cus ? 1 : 2);
+    long t = cus * per_cu / Hkv;
+    if (t < 1) t = 1;
+    c.target_items = (int)t;
+    const long by_cap = (long)B * ((max_kv_len + kPlanMaxChunk - 1) / kPlanMaxChunk);
+    const long mi = t + B > by_cap ? t + B : by_cap;
+    c.max_items = (int)mi;
+    c.hdr_bytes = 256;
+    c.req_bytes = round_up((size_t)B * 8, 256);
+    c.items_bytes = round_up((size_t)mi * 16, 256);
+    c.slots = (size_t)mi * max_q_len * Hq;
+    return c;
+}
 
 static size_t attn_smem_bytes(int NR, int NW, int NBUF, int chunk_keys)
 {
@@ -498,7 +701,11 @@ extern "C" size_t spec_verify_attn_workspace_bytes(int B, int M, int Hq, int Hkv
     const int ct = attn_chunk_target(B, Hkv, max_kv_len, attn_waves(NR) * 32);
     const size_t splits = (size_t)(max_kv_len + ct - 1) / ct;
     const size_t units = (size_t)M * Hq * splits;
-    return round_up(units * kD * 4, 256) + 2 * round_up(units * 4, 256);
+    const size_t fixed = round_up(units * kD * 4, 256) + 2 * round_up(units * 4, 256);
+    // the work-list mode has its own layout; the caller sizes the buffer before the mode is chosen
+    const AttnPlanCfg pc = attn_plan_cfg(B, Hq, Hkv, max_kv_len, max_q_len > 0 ? max_q_len : 1, NR, ct);
+    const size_t planned = pc.hdr_bytes + pc.req_bytes + pc.items_bytes + round_up(pc.slots * kD * 4, 256) + 2 * round_up(pc.slots * 4, 256);
+    return (B <= 1024 && planned > fixed) ? planned : fixed;
 }
 
 extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* v_cache,
@@ -542,14 +749,36 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
     p.out = (uint16_t*)out; p.lse = lse;
     p.splits = (max_kv_len + p.chunk_target - 1) / p.chunk_target;
     p.scale_log2e = scale * 1.4426950408889634f;
-    const size_t units = (size_t)M * Hq * p.splits;
-    char* ws = (char*)workspace;
-    p.part_o = (float*)ws;
-    p.part_m = (float*)(ws + round_up(units * kD * 4, 256));
-    p.part_l = (float*)(ws + round_up(units * kD * 4, 256) + round_up(units * 4, 256));
-
+    p.plan_hdr = nullptr; p.plan_req = nullptr; p.plan_items = nullptr;
     hipStream_t s = (hipStream_t)stream;
-    const dim3 grid(p.splits, Hkv, B);
+    char* ws = (char*)workspace;
+    const AttnPlanCfg pc = attn_plan_cfg(B, Hq, Hkv, max_kv_len, max_q_len, NR, p.chunk_target);
+    dim3 grid(p.splits, Hkv, B);
+    if (pc.on) {
+        if (pc.slots * kD > 2147483647u || (size_t)pc.max_items > 2147483647u)
+            return fail(SPEC_ESHAPE, "spec_verify_attn: work list beyond 32-bit slots");
+        int32_t* hdr = (int32_t*)ws;
+        int32_t* req = (int32_t*)(ws + pc.hdr_bytes);
+        int32_t* items = (int32_t*)(ws + pc.hdr_bytes + pc.req_bytes);
+        char* parts = ws + pc.hdr_bytes + pc.req_bytes + pc.items_bytes;
+        p.part_o = (float*)parts;
+        p.part_m = (float*)(parts + round_up(pc.slots * kD * 4, 256));
+        p.part_l = (float*)(parts + round_up(pc.slots * kD * 4, 256) + round_up(pc.slots * 4, 256));
+        hipLaunchKernelGGL(verify_attn_plan_kernel, dim3(1), dim3((B + 63) / 64 * 64), 0, s, p, B, pc.target_items, pc.step_keys,
+                           kPlanMinChunk, kPlanMaxChunk, pc.max_items, hdr, req, items);
+        int prc = check_launch("spec_verify_attn (plan)");
+        if (prc != SPEC_OK) return prc;
+        p.plan_hdr = hdr; p.plan_req = req; p.plan_items = items;
+        p.chunk_target = kPlanMaxChunk;                   // sizes the page-id staging area in LDS
+        p.splits = 2;                                     // "somebody is split": partials + merge kernel
+        grid = dim3(pc.max_items, Hkv, 1);
+    } else {
+        const size_t units = (size_t)M * Hq * p.splits;
+        p.part_o = (float*)ws;
+        p.part_m = (float*)(ws + round_up(units * kD * 4, 256));
+        p.part_l = (float*)(ws + round_up(units * kD * 4, 256) + round_up(units * 4, 256));
+    }
+
     int rc = SPEC_OK;
     switch (NR) {
         case 1: rc = launch_attn<1>(p, grid, s); break;
@@ -565,6 +794,9 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
     rc = check_launch("spec_verify_attn");
     if (rc != SPEC_OK) return rc;
     if (p.splits == 1) return SPEC_OK;                    // the main kernel wrote the output itself
-    hipLaunchKernelGGL(verify_attn_combine_kernel, dim3(M, Hq), dim3(256), 0, s, p, B);
+    // few pieces per request (typical count in work-list mode: items per request): one workgroup per row
+    const bool few = pc.on ? (pc.target_items + B) / B <= 8 : p.splits <= 8;
+    if (few) hipLaunchKernelGGL(verify_attn_combine_rows_kernel, dim3(M), dim3(256), 0, s, p, B);
+    else hipLaunchKernelGGL(verify_attn_combine_kernel, dim3(M, Hq), dim3(256), 0, s, p, B);
     return check_launch("spec_verify_attn (combine)");
 }

@@ -88,6 +88,63 @@ def test_attention_is_split_invariant(sv, oracle, chunk):
     _close(out.float().cpu().numpy(), _oracle_attn(oracle, b), f"chunk {chunk}", sharp=True)
 
 
+PLAN_CASES = ATTN_CASES + [
+    ("plan_split", 4, (0, 4, 8), ("uniform", 900, 2500), 8, 1, 1.0),
+    ("plan_long_few", 2, (4,), ("uniform", 5000, 9000), 8, 1, 1.0),
+    ("plan_gqa", 3, (2, 4), ("uniform", 600, 3000), 16, 4, 1.0),
+]
+
+
+@pytest.mark.parametrize("waves", [0, 3])
+@pytest.mark.parametrize("case", PLAN_CASES, ids=[c[0] for c in PLAN_CASES])
+def test_attention_with_balanced_work_list(sv, oracle, case, waves):
+    """The device-built work list (chunks sized from the real lengths, longest first) gives the same attention."""
+    name, B, gammas, ctx, Hq, Hkv, sq = case
+    cfg = wl.VerifyConfig(name, 21, B, gammas, ctx, Hq, Hkv, 64, 64, sigma_qkv=sq)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    sv.spec_set_tuning("attn_plan", 1)
+    sv.spec_set_tuning("attn_plan_waves", waves)
+    try:
+        step = _step(b, cfg)
+        step.attn_out.fill_(7.0)
+        out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
+        torch.cuda.synchronize()
+    finally:
+        sv.spec_set_tuning("attn_plan", 0)
+        sv.spec_set_tuning("attn_plan_waves", 0)
+    ref, ref_lse = _oracle_attn(oracle, b, want_lse=True)
+    _close(out.float().cpu().numpy(), ref, name, sharp=sq is not None)
+    np.testing.assert_allclose(step.lse.cpu().numpy(), ref_lse, rtol=2e-3, atol=2e-3)
+    assert int(step.status.cpu()) == 0
+
+
+def test_balanced_work_list_skips_and_flags_bad_requests(sv, oracle):
+    cfg = wl.VerifyConfig("bad_plan", 22, 4, (2,), ("uniform", 300, 1400), 8, 1, 64, 64, sigma_qkv=1.0)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    sv.spec_set_tuning("attn_plan", 1)
+    try:
+        step = _step(b, cfg)
+        sl = b["seq_lens"].clone()
+        sl[1] = b["max_kv_len"] + 100                  # longer than the bound the launch was sized for
+        step.attn_out.fill_(5.0)
+        out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], sl, b["qo_indptr"], b["scale"])
+        torch.cuda.synchronize()
+        assert int(step.status.cpu()) & sv.FLAG_BAD_LENGTH
+        qo = b["qo_indptr"].cpu().numpy()
+        assert (out[qo[1]:qo[2]].float() == 5.0).all()
+        ref = _oracle_attn(oracle, b)
+        keep = np.r_[0:qo[1], qo[2]:qo[4]]
+        _close(out.float().cpu().numpy()[keep], ref[keep], "others unaffected", sharp=True)
+        step.status.zero_()
+        pt = b["page_table"].clone()
+        pt[2, 3] = -1                                   # unmapped page inside request 2's range
+        step.attn(b["q"], b["k_cache"], b["v_cache"], pt, b["seq_lens"], b["qo_indptr"], b["scale"])
+        torch.cuda.synchronize()
+        assert int(step.status.cpu()) & sv.FLAG_BAD_PAGE
+    finally:
+        sv.spec_set_tuning("attn_plan", 0)
+
+
 def test_attention_needle_and_causality(sv, oracle):
     """A dominant key at candidate position c+2 must be seen by rows j >= 2 only (mask and page mapping)."""
     cfg = wl.VerifyConfig("needle", 13, 3, (4,), ("uniform", 100, 400), 8, 1, 64, 64)
