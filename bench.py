@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--config", default="mid", help="workload name in paper_2605_08151_amd.workloads.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-chunk", type=int, default=0, help="override keys per kv split (0 = library heuristic)")
+    ap.add_argument("--fused-stats", action="store_true",
+                    help="spec_lm_head_stats + spec_accept_stats instead of spec_lm_head + spec_accept (same outputs; "
+                         "measured slower on MI355X, see DESIGN.md)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (untimed): under rocprofv3 --pmc its FETCH_SIZE / "
                          "WRITE_SIZE readings calibrate the counters against a known byte count")
@@ -83,6 +86,7 @@ def main():
               for _ in range(total)]
 
     names = ("verify_attn", "lm_head", "accept", "kv_commit")
+    fused = args.fused_stats            # same outputs; greedy acceptance reads the LM head's block maxima instead of the logits
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
 
     def run(k, events=None):
@@ -91,9 +95,15 @@ def main():
         if events: events[0].record()
         step.attn(b["q"], kc, vc, pt, sl, qo, b["scale"], want_lse=False)
         if events: events[1].record()
-        step.lm_head(b["hidden"], b["W"])
+        if fused:
+            step.lm_head_stats(b["hidden"], b["W"])
+        else:
+            step.lm_head(b["hidden"], b["W"])
         if events: events[2].record()
-        step.accept(tokens, draft_probs, b["temperature"], seeds, 0, qo)
+        if fused:
+            step.accept_stats(tokens, draft_probs, b["temperature"], seeds, 0, qo)
+        else:
+            step.accept(tokens, draft_probs, b["temperature"], seeds, 0, qo)
         if events: events[3].record()
         step.commit(pt, sl, qo, fl, fc, cfg.P)
         if events: events[4].record()

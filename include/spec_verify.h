@@ -119,6 +119,26 @@ int spec_verify_attn(const void* q, const void* k_cache, const void* v_cache,
 int spec_lm_head(const void* hidden, const void* W, float* logits, int M, int H, int V, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * spec_lm_head_stats — spec_lm_head that also leaves, for every row, the
+ * maximum of each vocabulary block it computed and that maximum's lowest
+ * index, so that greedy acceptance (temperature 0, the paper's default
+ * setting: Experiments, "greedy decoding") need not read the logits again.
+ * Same operation and passage as spec_lm_head; the statistics are what
+ * spec_accept_stats consumes.
+ *   blocks = spec_lm_head_stats_blocks(M, H, V) (host): blocks per row, 0 when
+ *     the shape is not served by the fused kernel (then this call is exactly
+ *     spec_lm_head, blk_max/blk_arg are not touched and may be NULL).
+ *   blk_max [M, blocks] fp32, blk_arg [M, blocks] int32 (device, caller-owned):
+ *     blocks cover increasing vocabulary ranges; a block that holds a NaN has
+ *     blk_max = NaN; a block without entries has -inf and INT32_MAX.
+ * Errors as spec_lm_head.
+ * ------------------------------------------------------------------------- */
+int spec_lm_head_stats_blocks(int M, int H, int V);
+
+int spec_lm_head_stats(const void* hidden, const void* W, float* logits, int M, int H, int V,
+                       float* blk_max, int32_t* blk_arg, void* stream);
+
+/* ---------------------------------------------------------------------------
  * spec_accept — accepted length and bonus token per request (Method,
  * "Rollback-Based Mode Selection": after the verification pass the target
  * performs rejection sampling and identifies the rollback set).
@@ -156,6 +176,19 @@ int spec_accept(const float* logits, const int32_t* tokens, const float* draft_p
                 int B, int M, int V, int gamma_max,
                 int32_t* status_flags,
                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* spec_accept with the block statistics of spec_lm_head_stats (blk_max, blk_arg, blocks as described there;
+ * blocks == 0: identical to spec_accept).  Requests with temperature 0 take their row maxima from the
+ * statistics; the logits of their rows are not read.  Sampled requests are handled as in spec_accept.  With
+ * seeds == NULL (all requests greedy) no logits are read at all.  Same outputs, flags and errors. */
+int spec_accept_stats(const float* logits, const int32_t* tokens, const float* draft_probs,
+                      const float* temperature, const uint64_t* seeds, uint32_t round,
+                      const int32_t* qo_indptr,
+                      int32_t* accept_len, int32_t* out_tokens, uint8_t* rollback, int32_t* stats,
+                      int B, int M, int V, int gamma_max,
+                      const float* blk_max, const int32_t* blk_arg, int blocks,
+                      int32_t* status_flags,
+                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
  * spec_next_mode — execution mode of round n+1 (Method, "Rollback-Based Mode

@@ -18,6 +18,7 @@ EXPORTS = (
     "spec_last_error_string", "spec_version", "spec_set_tuning",
     "spec_verify_attn_workspace_bytes", "spec_verify_attn", "spec_lm_head",
     "spec_accept_workspace_bytes", "spec_accept", "spec_kv_commit", "spec_next_mode",
+    "spec_lm_head_stats_blocks", "spec_lm_head_stats", "spec_accept_stats",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -52,6 +53,12 @@ def _load():
     lib.spec_accept.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.spec_kv_commit.restype = i32
     lib.spec_kv_commit.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp]
+    lib.spec_lm_head_stats_blocks.restype = i32
+    lib.spec_lm_head_stats_blocks.argtypes = [i32] * 3
+    lib.spec_lm_head_stats.restype = i32
+    lib.spec_lm_head_stats.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.spec_accept_stats.restype = i32
+    lib.spec_accept_stats.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
     lib.spec_next_mode.restype = i32
     lib.spec_next_mode.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                    ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -124,6 +131,18 @@ def spec_lm_head(hidden, W, logits):
                              M, H, V, _stream()))
 
 
+def spec_lm_head_stats_blocks(M, H, V):
+    return int(_lib.spec_lm_head_stats_blocks(int(M), int(H), int(V)))
+
+
+def spec_lm_head_stats(hidden, W, logits, blk_max, blk_arg):
+    M, H = hidden.shape
+    V = W.shape[0]
+    assert W.shape[1] == H and tuple(logits.shape) == (M, V)
+    _check(_lib.spec_lm_head_stats(_ptr(hidden, torch.bfloat16), _ptr(W, torch.bfloat16), _ptr(logits, torch.float32),
+                                   M, H, V, _ptr(blk_max, torch.float32), _ptr(blk_arg, torch.int32), _stream()))
+
+
 def spec_accept_workspace_bytes(B, M, V, gamma_max):
     return int(_lib.spec_accept_workspace_bytes(B, M, V, gamma_max))
 
@@ -138,6 +157,22 @@ def spec_accept(logits, tokens, draft_probs, temperature, seeds, round_, qo_indp
         _ptr(temperature, torch.float32), _ptr(seeds, torch.int64), int(round_), _ptr(qo_indptr, torch.int32),
         _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), _ptr(rollback, torch.uint8),
         _ptr(stats, torch.int32), B, M, V, int(gamma_max), _ptr(status_flags, torch.int32),
+        _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
+
+
+def spec_accept_stats(logits, tokens, draft_probs, temperature, seeds, round_, qo_indptr, accept_len, out_tokens, rollback,
+                      stats, gamma_max, blk_max, blk_arg, blocks, status_flags, workspace):
+    M, V = logits.shape
+    B = qo_indptr.shape[0] - 1
+    assert tuple(out_tokens.shape) == (B, gamma_max + 1)
+    assert blocks == 0 or (tuple(blk_max.shape) == (M, blocks) and tuple(blk_arg.shape) == (M, blocks))
+    _check(_lib.spec_accept_stats(
+        _ptr(logits, torch.float32), _ptr(tokens, torch.int32), _ptr(draft_probs, torch.float32),
+        _ptr(temperature, torch.float32), _ptr(seeds, torch.int64), int(round_), _ptr(qo_indptr, torch.int32),
+        _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), _ptr(rollback, torch.uint8),
+        _ptr(stats, torch.int32), B, M, V, int(gamma_max),
+        _ptr(blk_max, torch.float32) if blocks else None, _ptr(blk_arg, torch.int32) if blocks else None, int(blocks),
+        _ptr(status_flags, torch.int32),
         _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
 
 

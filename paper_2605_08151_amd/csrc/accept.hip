@@ -126,7 +126,7 @@ constexpr int kSegPerWg = 1;        // consecutive segments one workgroup handle
 __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
     const float* __restrict__ logits, const float* __restrict__ temperature,
     const int32_t* __restrict__ qo_indptr, int B, int V, int nseg, bool vec,
-    AcceptWorkspace w, int32_t* __restrict__ stats)
+    AcceptWorkspace w, int32_t* __restrict__ stats, bool greedy_rows_covered)
 {
     __shared__ float s_m[kSegPerWg][kThreads / 64];
     __shared__ int s_a[kSegPerWg][kThreads / 64];
@@ -142,6 +142,7 @@ __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
         load_strided(lrow, min(v0, V), min(V, v0 + kSeg), vec, tid, x[q]);      // past the row: all -inf
     }
     const float T = temperature[find_request(qo_indptr, B, row)];
+    if (greedy_rows_covered && T == 0.0f) return;         // the decision reads the LM head's block statistics instead
 #pragma unroll
     for (int q = 0; q < kSegPerWg; ++q) {
         const int v0 = (seg0 + q) * kSeg;
@@ -199,13 +200,20 @@ __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
     }
 }
 
+// Counter reset for batches in which row_stats is not launched at all.
+__global__ void accept_reset_stats_kernel(int32_t* __restrict__ stats, int B)
+{
+    if (threadIdx.x < 4) stats[threadIdx.x] = (threadIdx.x == 2) ? B : 0;
+}
+
 // ---- 2. per-request decision -----------------------------------------------------------------
 __global__ __launch_bounds__(256) void accept_decide_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ tokens, const float* __restrict__ draft_probs,
     const float* __restrict__ temperature, const uint64_t* __restrict__ seeds, uint32_t round,
     const int32_t* __restrict__ qo_indptr, int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens,
     uint8_t* __restrict__ rollback, int32_t* __restrict__ stats, int M, int V, int nseg, int gamma_max,
-    AcceptWorkspace w, int32_t* __restrict__ status_flags)
+    AcceptWorkspace w, int32_t* __restrict__ status_flags,
+    const float* __restrict__ blk_max, const int32_t* __restrict__ blk_arg, int nblk)
 {
     __shared__ double s_m[kMaxRows], s_z[kMaxRows];
     __shared__ int s_arg[kMaxRows], s_bad[kMaxRows];
@@ -220,10 +228,30 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
     }
     const float T = temperature[i];
     const double Td = (double)T;
+    const bool from_blocks = nblk > 0 && T == 0.0f;        // greedy: maxima the LM head left per vocabulary block
     for (int j = wave; j <= gamma; j += 4) {               // rows are merged by the four waves in parallel
         const size_t base = (size_t)(r0 + j) * nseg;
         float m = -INFINITY;
         int arg = 0x7FFFFFFF, bad = 0;
+        if (from_blocks) {
+            // ~V/128 blocks per row: eight loads in flight per lane, or the walk is one memory latency per 64 blocks
+            const size_t bb = (size_t)(r0 + j) * nblk;
+            for (int s0 = lane; s0 < nblk; s0 += 64 * 8) {
+                float sm[8];
+                int sa[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int s = s0 + 64 * u;
+                    sm[u] = s < nblk ? blk_max[bb + s] : -INFINITY;
+                    sa[u] = s < nblk ? blk_arg[bb + s] : 0x7FFFFFFF;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    bad |= (sm[u] != sm[u]);
+                    if (sm[u] > m || (sm[u] == m && sa[u] < arg)) { m = sm[u]; arg = sa[u]; }
+                }
+            }
+        } else
         for (int s = lane; s < nseg; s += 64) {
             const float sm = w.seg_max[base + s];
             const int sa = w.seg_arg[base + s];
@@ -453,18 +481,20 @@ extern "C" size_t spec_accept_workspace_bytes(int B, int M, int V, int gamma_max
     return specv::carve(&w, nullptr, B, M, accept_nseg(V));
 }
 
-extern "C" int spec_accept(const float* logits, const int32_t* tokens, const float* draft_probs,
-                           const float* temperature, const uint64_t* seeds, uint32_t round,
-                           const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
-                           uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
-                           int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
+extern "C" int spec_accept_stats(const float* logits, const int32_t* tokens, const float* draft_probs,
+                                 const float* temperature, const uint64_t* seeds, uint32_t round,
+                                 const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
+                                 uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                                 const float* blk_max, const int32_t* blk_arg, int blocks,
+                                 int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
 {
     using namespace specv;
-    if (B < 0 || M < 0 || V <= 0 || gamma_max < 0)
-        return fail(SPEC_EINVAL, "spec_accept: negative size (B=%d M=%d V=%d gamma_max=%d)", B, M, V, gamma_max);
+    if (B < 0 || M < 0 || V <= 0 || gamma_max < 0 || blocks < 0)
+        return fail(SPEC_EINVAL, "spec_accept: negative size (B=%d M=%d V=%d gamma_max=%d blocks=%d)", B, M, V, gamma_max, blocks);
     if (B == 0) return SPEC_OK;
     if (!logits || !tokens || !temperature || !qo_indptr || !accept_len || !out_tokens)
         return fail(SPEC_EINVAL, "spec_accept: NULL pointer argument");
+    if (blocks > 0 && (!blk_max || !blk_arg)) return fail(SPEC_EINVAL, "spec_accept_stats: blocks > 0 but no block statistics");
     if (gamma_max + 1 > kMaxRows)
         return fail(SPEC_ESHAPE, "spec_accept: gamma_max=%d, at most %d candidate rows per request", gamma_max, kMaxRows);
     if (M < B) return fail(SPEC_EINVAL, "spec_accept: M=%d < B=%d (every request has at least one row)", M, B);
@@ -480,10 +510,16 @@ extern "C" int spec_accept(const float* logits, const int32_t* tokens, const flo
     carve(&w, (char*)workspace, B, M, nseg);
     const bool vec = (V % 4 == 0) && aligned(logits, 16) && (!draft_probs || aligned(draft_probs, 16));
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(accept_row_stats_kernel, dim3((nseg + kSegPerWg - 1) / kSegPerWg, M), dim3(kThreads), 0, s, logits, temperature, qo_indptr, B,
-                       V, nseg, vec, w, stats);
+    if (blocks > 0 && !seeds) {
+        // all greedy (seeds == NULL promises it) and every row's maxima are at hand: the logits are not read at all
+        if (stats) hipLaunchKernelGGL(accept_reset_stats_kernel, dim3(1), dim3(64), 0, s, stats, B);
+    } else {
+        hipLaunchKernelGGL(accept_row_stats_kernel, dim3((nseg + kSegPerWg - 1) / kSegPerWg, M), dim3(kThreads), 0, s, logits, temperature,
+                           qo_indptr, B, V, nseg, vec, w, stats, blocks > 0);
+    }
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(256), 0, s, logits, tokens, draft_probs, temperature, seeds,
-                       round, qo_indptr, accept_len, out_tokens, rollback, stats, M, V, nseg, gamma_max, w, status_flags);
+                       round, qo_indptr, accept_len, out_tokens, rollback, stats, M, V, nseg, gamma_max, w, status_flags,
+                       blk_max, blk_arg, blocks);
     if (seeds) {   // seeds == NULL promises an all-greedy batch: nothing is ever drawn
         hipLaunchKernelGGL(accept_residual_sums_kernel, dim3(nseg, B), dim3(kThreads), 0, s, logits, draft_probs, V,
                            nseg, vec, w);
@@ -491,4 +527,15 @@ extern "C" int spec_accept(const float* logits, const int32_t* tokens, const flo
                            out_tokens, V, nseg, gamma_max, w);
     }
     return check_launch("spec_accept");
+}
+
+extern "C" int spec_accept(const float* logits, const int32_t* tokens, const float* draft_probs,
+                           const float* temperature, const uint64_t* seeds, uint32_t round,
+                           const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
+                           uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                           int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return spec_accept_stats(logits, tokens, draft_probs, temperature, seeds, round, qo_indptr, accept_len, out_tokens,
+                             rollback, stats, B, M, V, gamma_max, nullptr, nullptr, 0, status_flags, workspace,
+                             workspace_bytes, stream);
 }

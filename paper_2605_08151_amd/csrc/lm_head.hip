@@ -131,10 +131,14 @@ constexpr int kPassCols = 128;               // vocabulary entries per workgroup
 // TM: 16-row tiles of hidden in total; MS: wave rows (the 4*MS waves form a 4 x MS grid: wave column = 32
 // vocabulary entries, wave row = TM/MS row tiles; with MS = 2 two waves share every SIMD and hide each other's
 // load latency); RS: depth of the W register ring in 128-k slabs; PAIR: refill two chunks at a time.
-template <int TM, int MS, int RS, int PAIR>
+// STATS: also leave, per row and per pass of the workgroup (block b = workgroup * passes_per_wg + pass), the maximum
+// of the block's logits and its lowest index (NaN and INT_MAX if the block holds a NaN; -inf and INT_MAX for a
+// block without entries), so that greedy acceptance need not read the logits again.
+template <int TM, int MS, int RS, int PAIR, bool STATS>
 __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
-    int M, int H, int V, int cols_per_wg, bool vec_store)
+    int M, int H, int V, int cols_per_wg, bool vec_store,
+    float* __restrict__ blk_max, int32_t* __restrict__ blk_arg, int nblk, int passes_per_wg)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int TN = 2;                             // 16-entry tiles of W per wave
@@ -150,6 +154,7 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
     const int c_begin = blockIdx.x * cols_per_wg;
     const int c_end = min(V, c_begin + cols_per_wg);
     if (c_begin >= c_end) return;
+    int pass_index = 0;
 
     f32x4 acc[TN][TMH];
 #pragma unroll
@@ -270,6 +275,50 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
             __builtin_amdgcn_sched_barrier(0);
         }
         // acc[tn][tm][i] = C[row hrow0 + 16tm][entry st_c0 + 16tn + 4kg + i]
+        if (STATS) {
+            // every wave has left the last slab through a barrier, so the hidden buffers are free: buf1 takes 16
+            // candidates per row (4 waves x 4 lane groups), each the best of a lane's 8 entries
+            float* cand_v = reinterpret_cast<float*>(buf1);
+            int* cand_i = reinterpret_cast<int*>(buf1 + BM * 16 * 4);
+#pragma unroll
+            for (int tm = 0; tm < TMH; ++tm) {
+                float best = -INFINITY;
+                int bi = 0x7FFFFFFF;
+                bool nan = false;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int e = tn * 16 + kg * 4 + i;
+                        const float v = acc[tn][tm][i];
+                        if (e < st_nc) {
+                            nan |= (v != v);
+                            if (v > best) { best = v; bi = st_c0 + e; }
+                        }
+                    }
+                const int slot = (hrow0 + tm * 16) * 16 + wave * 4 + kg;
+                cand_v[slot] = nan ? __builtin_nanf("") : best;
+                cand_i[slot] = bi;
+            }
+            __syncthreads();
+            for (int r = tid; r < M; r += kThreads) {
+                float best = -INFINITY;
+                int bi = 0x7FFFFFFF;
+                bool nan = false;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const float v = cand_v[r * 16 + q];
+                    const int vi = cand_i[r * 16 + q];
+                    nan |= (v != v);
+                    if (v > best || (v == best && vi < bi)) { best = v; bi = vi; }
+                }
+                const size_t o = (size_t)r * nblk + (size_t)blockIdx.x * passes_per_wg + pass_index;
+                blk_max[o] = nan ? __builtin_nanf("") : best;
+                blk_arg[o] = nan ? 0x7FFFFFFF : bi;
+            }
+            ++pass_index;
+            // (the candidates are read before the next barrier, which precedes the next write to buf1)
+        }
 #pragma unroll
         for (int tm = 0; tm < TMH; ++tm) {
             const int row = hrow0 + tm * 16;
@@ -290,6 +339,16 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
             }
         }
         if (!more) break;
+    }
+    if (STATS) {
+        // blocks of passes this workgroup did not have (the last workgroup's range may be shorter)
+        const int missing = passes_per_wg - pass_index;
+        for (int e = tid; e < missing * M; e += kThreads) {
+            const int r = e / missing, q = e - r * missing;
+            const size_t o = (size_t)r * nblk + (size_t)blockIdx.x * passes_per_wg + pass_index + q;
+            blk_max[o] = -INFINITY;
+            blk_arg[o] = 0x7FFFFFFF;
+        }
     }
 }
 
@@ -440,24 +499,35 @@ static int device_cu_count()
     return cus;
 }
 
-template <int TM, int MS, int RS, int PAIR = 0>
-static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
+// vocabulary entries per workgroup and the grid of the weight-streaming kernel
+static void skinny_geometry(int V, int* cols, int* grid)
+{
+    const int cus = device_cu_count();
+    int c = ((V + cus - 1) / cus + 3) & ~3;
+    if (c < 64) c = 64;
+    *cols = c;
+    *grid = (V + c - 1) / c;
+}
+
+template <int TM, int MS, int RS, int PAIR = 0, bool STATS = false>
+static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s,
+                         float* blk_max = nullptr, int32_t* blk_arg = nullptr)
 {
     constexpr int BM = (TM + MS - 1) / MS * MS * 16;
     const size_t smem = 2 * (size_t)BM * kHPitch;
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM, MS, RS, PAIR>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM, MS, RS, PAIR, STATS>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
         configured = true;
     }
-    const int cus = device_cu_count();
-    int cols = ((V + cus - 1) / cus + 3) & ~3;
-    if (cols < 64) cols = 64;
-    const int grid = (V + cols - 1) / cols;
+    int cols, grid;
+    skinny_geometry(V, &cols, &grid);
+    const int ppw = (cols + kPassCols - 1) / kPassCols;
     const bool vec_store = (V % 4 == 0);
-    hipLaunchKernelGGL((lm_head_skinny_kernel<TM, MS, RS, PAIR>), dim3(grid), dim3(256 * MS), smem, s, a, w, c, M, H, V, cols, vec_store);
+    hipLaunchKernelGGL((lm_head_skinny_kernel<TM, MS, RS, PAIR, STATS>), dim3(grid), dim3(256 * MS), smem, s, a, w, c, M, H, V, cols,
+                       vec_store, blk_max, blk_arg, grid * ppw, ppw);
     return SPEC_OK;
 }
 
@@ -474,7 +544,45 @@ static int launch_skinny_auto(const uint16_t* a, const uint16_t* w, float* c, in
     return launch_skinny<TM, 1, 2, 1>(a, w, c, M, H, V, s);
 }
 
+static bool skinny_applies(int M, int H)
+{
+    const int force = g_lm_kernel;
+    return (force == 0 || force == 1 || force >= 4) && M <= 160 && H % (4 * kSlab) == 0;
+}
+
 }  // namespace specv
+
+/* blocks per row of the statistics spec_lm_head_stats writes; 0 = this shape is not served by the fused kernel */
+extern "C" int spec_lm_head_stats_blocks(int M, int H, int V)
+{
+    using namespace specv;
+    if (M <= 0 || H <= 0 || V <= 0 || !skinny_applies(M, H) || g_lm_kernel >= 4) return 0;
+    int cols, grid;
+    skinny_geometry(V, &cols, &grid);
+    return grid * ((cols + kPassCols - 1) / kPassCols);
+}
+
+extern "C" int spec_lm_head_stats(const void* hidden, const void* W, float* logits, int M, int H, int V,
+                                  float* blk_max, int32_t* blk_arg, void* stream)
+{
+    using namespace specv;
+    const int blocks = spec_lm_head_stats_blocks(M, H, V);
+    if (blocks == 0) return spec_lm_head(hidden, W, logits, M, H, V, stream);
+    if (!hidden || !W || !logits || !blk_max || !blk_arg) return fail(SPEC_EINVAL, "spec_lm_head_stats: NULL pointer argument");
+    if (!aligned(hidden, 16) || !aligned(W, 16) || !aligned(logits, 16))
+        return fail(SPEC_EINVAL, "spec_lm_head_stats: operands must be 16-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    const uint16_t* a = (const uint16_t*)hidden;
+    const uint16_t* w = (const uint16_t*)W;
+    int rc;
+    if (M <= 32) rc = launch_skinny<2, 1, 2, 1, true>(a, w, logits, M, H, V, s, blk_max, blk_arg);
+    else if (M <= 64) rc = launch_skinny<4, 1, 2, 1, true>(a, w, logits, M, H, V, s, blk_max, blk_arg);
+    else if (M <= 96) rc = launch_skinny<6, 1, 2, 1, true>(a, w, logits, M, H, V, s, blk_max, blk_arg);
+    else if (M <= 128) rc = launch_skinny<8, 1, 2, 1, true>(a, w, logits, M, H, V, s, blk_max, blk_arg);
+    else rc = launch_skinny<10, 1, 2, 1, true>(a, w, logits, M, H, V, s, blk_max, blk_arg);
+    if (rc != SPEC_OK) return rc;
+    return check_launch("spec_lm_head_stats");
+}
 
 extern "C" int spec_lm_head(const void* hidden, const void* W, float* logits, int M, int H, int V, void* stream)
 {
@@ -489,7 +597,7 @@ extern "C" int spec_lm_head(const void* hidden, const void* W, float* logits, in
     const uint16_t* a = (const uint16_t*)hidden;
     const uint16_t* w = (const uint16_t*)W;
     const int force = g_lm_kernel;
-    if ((force == 0 || force == 1 || force >= 4) && M <= 160 && H % (4 * kSlab) == 0) {
+    if (skinny_applies(M, H)) {
         int rc;
         if (M <= 32) rc = launch_skinny_auto<2>(a, w, logits, M, H, V, s);
         else if (M <= 64) rc = launch_skinny_auto<4>(a, w, logits, M, H, V, s);

@@ -25,6 +25,10 @@ class VerifyStep:
         self.rollback = torch.empty(B, dtype=torch.uint8, device=dev)
         self.stats = torch.zeros(4, dtype=torch.int32, device=dev)
         self.status = torch.zeros(1, dtype=torch.int32, device=dev)
+        # block statistics of the fused LM head (0 blocks: the shape has none and acceptance scans the logits)
+        self.blocks = sv.spec_lm_head_stats_blocks(M, H, V)
+        self.blk_max = torch.empty((M, max(1, self.blocks)), dtype=torch.float32, device=dev)
+        self.blk_arg = torch.empty((M, max(1, self.blocks)), dtype=torch.int32, device=dev)
 
     def attn(self, q, k_cache, v_cache, page_table, seq_lens, qo_indptr, scale, want_lse=True):
         sv.spec_verify_attn(q, k_cache, v_cache, page_table, seq_lens, qo_indptr, self.attn_out,
@@ -35,6 +39,16 @@ class VerifyStep:
     def lm_head(self, hidden, W):
         sv.spec_lm_head(hidden, W, self.logits)
         return self.logits
+
+    def lm_head_stats(self, hidden, W):
+        sv.spec_lm_head_stats(hidden, W, self.logits, self.blk_max, self.blk_arg)
+        return self.logits
+
+    def accept_stats(self, tokens, draft_probs, temperature, seeds, round_, qo_indptr):
+        sv.spec_accept_stats(self.logits, tokens, draft_probs, temperature, seeds, round_, qo_indptr, self.accept_len,
+                             self.out_tokens, self.rollback, self.stats, self.gamma_max, self.blk_max, self.blk_arg,
+                             self.blocks, self.status, self.accept_ws)
+        return self.accept_len, self.out_tokens
 
     def accept(self, tokens, draft_probs, temperature, seeds, round_, qo_indptr, logits=None):
         sv.spec_accept(self.logits if logits is None else logits, tokens, draft_probs, temperature, seeds, round_,

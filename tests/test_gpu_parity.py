@@ -395,12 +395,12 @@ def test_empty_batch_calls_are_noops(sv):
 
 
 # --------------------------------------------------------------------------- whole step
-def _run_step(sv, oracle, cfg, stochastic):
+def _run_step(sv, oracle, cfg, stochastic, fused=False):
     b = wl.make_batch(cfg, device="cuda")
     step = _step(b, cfg)
     qo = b["qo_indptr"].cpu().numpy()
     out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
-    logits = step.lm_head(b["hidden"], b["W"])
+    logits = step.lm_head_stats(b["hidden"], b["W"]) if fused else step.lm_head(b["hidden"], b["W"])
     torch.cuda.synchronize()
     ref_attn = _oracle_attn(oracle, b)                   # before the commit changes lengths and pages
     gl = logits.cpu().numpy()
@@ -413,7 +413,11 @@ def _run_step(sv, oracle, cfg, stochastic):
         per_row_T = np.repeat(temp, np.diff(qo))
         tokens = torch.where(torch.from_numpy(per_row_T > 0), tokens_s, tokens_g)
     seeds = b["seeds"]
-    step.accept(tokens.cuda(), dp, b["temperature"], seeds, 5, b["qo_indptr"])
+    if fused:
+        # an all-greedy batch may pass no seeds: then no logits are read at all
+        step.accept_stats(tokens.cuda(), dp, b["temperature"], seeds if stochastic else None, 5, b["qo_indptr"])
+    else:
+        step.accept(tokens.cuda(), dp, b["temperature"], seeds, 5, b["qo_indptr"])
     torch.cuda.synchronize()
     ref = oracle.accept(gl, tokens.numpy(), None if dp is None else dp.cpu().numpy(), temp,
                         seeds.cpu().numpy().view(np.uint64), 5, qo, b["gamma_max"])
@@ -446,6 +450,73 @@ def test_whole_step_small_hybrid_mix(sv, oracle):
     b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=True)
     _close(out.float().cpu().numpy(), ref_attn, "hybrid attn", sharp=True)
     _close(gl, oracle.lm_head(wl.bf16_bits(b["hidden"]), wl.bf16_bits(b["W"])), "hybrid logits")
+
+
+@pytest.mark.parametrize("M,H,V", [(20, 1024, 32000), (7, 512, 1013), (33, 512, 4097), (160, 512, 20011), (128, 1024, 9000)])
+def test_fused_lm_head_statistics(sv, oracle, M, H, V):
+    """spec_lm_head_stats: same logits as spec_lm_head (bitwise), and block maxima whose merge is each row's
+    maximum and its lowest index."""
+    g = torch.Generator(device="cuda").manual_seed(M + V)
+    hidden = torch.randn((M, H), generator=g, device="cuda").to(torch.bfloat16)
+    W = (torch.randn((V, H), generator=g, device="cuda") / math.sqrt(H)).to(torch.bfloat16)
+    W[V // 3] = W[V // 2]                                  # an exact tie between two vocabulary entries
+    blocks = sv.spec_lm_head_stats_blocks(M, H, V)
+    assert blocks > 0
+    plain = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    fused = torch.full((M, V), 3.0, dtype=torch.float32, device="cuda")
+    bm = torch.full((M, blocks), 7.0, dtype=torch.float32, device="cuda")
+    ba = torch.full((M, blocks), -5, dtype=torch.int32, device="cuda")
+    sv.spec_lm_head(hidden, W, plain)
+    sv.spec_lm_head_stats(hidden, W, fused, bm, ba)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, fused)
+    gl, bmn, ban = fused.cpu().numpy(), bm.cpu().numpy(), ba.cpu().numpy()
+    assert not np.isnan(bmn).any()
+    np.testing.assert_array_equal(bmn.max(axis=1), gl.max(axis=1))
+    for r in range(M):
+        best = bmn[r].max()
+        assert ban[r][bmn[r] == best].min() == int(np.flatnonzero(gl[r] == best)[0])   # lowest index among ties
+        real = bmn[r] > -np.inf
+        assert (gl[r][ban[r][real]] == bmn[r][real]).all()                               # every block names its own maximum
+        assert (np.diff(ban[r][real]) > 0).all()                                          # blocks cover increasing ranges
+    ref = oracle.lm_head(wl.bf16_bits(hidden), wl.bf16_bits(W))
+    _close(gl, ref, "fused logits", sharp=True)
+
+
+def test_fused_statistics_carry_nan_rows(sv, oracle):
+    """A NaN in a hidden row makes that row's logits NaN: flagged through the block statistics exactly as by the scan."""
+    cfg = wl.VerifyConfig("nanrow", 31, 6, (2,), ("const", 40), 8, 1, 512, 5003)
+    b = wl.make_batch(cfg, device="cuda")
+    b["hidden"][4, 7] = float("nan")                      # request 1, row 1
+    results = []
+    for fused in (False, True):
+        step = _step(b, cfg)
+        logits = step.lm_head_stats(b["hidden"], b["W"]) if fused else step.lm_head(b["hidden"], b["W"])
+        torch.cuda.synchronize()
+        tokens, _ = wl.draft_tokens_greedy(cfg, b["qo_indptr"], torch.nan_to_num(logits).argmax(1).cpu())
+        (step.accept_stats if fused else step.accept)(tokens.cuda(), None, b["temperature"], None, 0, b["qo_indptr"])
+        torch.cuda.synchronize()
+        assert int(step.status.cpu()) & sv.FLAG_BAD_LOGITS
+        results.append((step.accept_len.cpu().numpy(), step.out_tokens.cpu().numpy(), step.rollback.cpu().numpy(),
+                        step.stats.cpu().numpy()))
+    for x, y in zip(*results):
+        assert np.array_equal(x, y)
+    assert results[1][0][1] == 0 and (results[1][1][1] == -1).all()
+    ref = oracle.accept(logits.cpu().numpy(), tokens.numpy(), None, b["temperature"].cpu().numpy(), None, 0,
+                        b["qo_indptr"].cpu().numpy(), b["gamma_max"])
+    assert np.array_equal(results[1][0], ref["accept_len"]) and np.array_equal(results[1][1], ref["out_tokens"])
+
+
+@pytest.mark.parametrize("name,stochastic", [("tiny", False), ("mid", False), ("hybrid_small", True)])
+def test_whole_step_with_fused_statistics(sv, oracle, name, stochastic):
+    """The step through spec_lm_head_stats + spec_accept_stats: same integers as the oracle on the GPU's logits
+    (greedy requests decided from block maxima, sampled ones from the scan, in one batch for the mix)."""
+    cfg = wl.CONFIGS[name] if name in wl.CONFIGS else wl.VerifyConfig(
+        "hybrid_small", 21, 24, (0, 2, 4, 8), ("lognormal", 600, 1.0, 32, 4000), 8, 1, 512, 20000,
+        temperature=("alternate", 0.0, 1.0), sigma_qkv=1.0)
+    b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=stochastic, fused=True)
+    assert step.blocks > 0
+    _close(out.float().cpu().numpy(), ref_attn, f"{name} attn", sharp=name == "hybrid_small")
 
 
 # --------------------------------------------------------------------------- BASELINE configurations at full size
