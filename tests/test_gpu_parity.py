@@ -519,6 +519,73 @@ def test_whole_step_with_fused_statistics(sv, oracle, name, stochastic):
     _close(out.float().cpu().numpy(), ref_attn, f"{name} attn", sharp=name == "hybrid_small")
 
 
+# --------------------------------------------------------------------------- determinism, bounds, large batches
+def test_results_are_bitwise_repeatable_and_stay_inside_their_buffers(sv, oracle):
+    """Three runs of attention (split, work list and unsplit), LM head and stochastic acceptance give identical bits,
+    and guard bands around every output keep their fill pattern (no write outside the tensors handed in)."""
+    cfg = wl.VerifyConfig("rep", 41, 12, (0, 2, 4, 8), ("uniform", 300, 3000), 8, 1, 512, 20011,
+                          temperature=("alternate", 0.0, 0.8), sigma_qkv=1.0)
+    b = wl.make_batch(cfg, device="cuda")
+    M, V, B = b["M"], cfg.V, b["B"]
+    guard = 64
+
+    def guarded(shape, dtype, fill):
+        n = int(np.prod(shape))
+        flat = torch.full((n + 2 * guard,), fill, dtype=dtype, device="cuda")
+        return flat, flat[guard:guard + n].view(shape)
+
+    runs = []
+    for tuning in ({"attn_plan": 2, "attn_chunk": 0}, {"attn_plan": 1}, {"attn_plan": 2, "attn_chunk": 100000}):
+        for k, v in tuning.items():
+            sv.spec_set_tuning(k, v)
+        try:
+            outs = []
+            for rep in range(3):
+                step = _step(b, cfg)
+                of, step.attn_out = guarded((M, cfg.Hq, cfg.D), torch.bfloat16, 9.0)
+                lf, step.logits = guarded((M, V), torch.float32, 9.0)
+                af, step.accept_len = guarded((B,), torch.int32, -77)
+                tf, step.out_tokens = guarded((B, b["gamma_max"] + 1), torch.int32, -77)
+                step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
+                step.lm_head(b["hidden"], b["W"])
+                torch.cuda.synchronize()
+                if rep == 0 and not runs:
+                    dp, tokens_s = wl.draft_probs_noisy(cfg, b["qo_indptr"], step.logits)
+                step.accept(tokens_s.cuda(), dp, b["temperature"], b["seeds"], 3, b["qo_indptr"])
+                torch.cuda.synchronize()
+                for flat, fill in ((of, 9.0), (lf, 9.0), (af, -77), (tf, -77)):
+                    assert (flat[:guard] == fill).all() and (flat[-guard:] == fill).all()
+                outs.append((step.attn_out.clone(), step.lse.clone(), step.logits.clone(), step.accept_len.clone(),
+                             step.out_tokens.clone()))
+            for other in outs[1:]:
+                for x, y in zip(outs[0], other):
+                    assert torch.equal(x, y)
+            runs.append(outs[0])
+        finally:
+            for k in tuning:
+                sv.spec_set_tuning(k, 0)
+    # the three decompositions agree to the tolerance, the integer results exactly
+    ref = _oracle_attn(oracle, b)
+    for r in runs:
+        _close(r[0].float().cpu().numpy(), ref, "decomposition", sharp=True)
+        assert torch.equal(r[3], runs[0][3]) and torch.equal(r[4], runs[0][4])
+
+
+def test_attention_with_more_requests_than_the_work_list_takes(sv, oracle):
+    """B > 1024: the fixed-chunk path serves it even when the work list is asked for."""
+    cfg = wl.VerifyConfig("manyreq", 42, 1100, (0, 1), ("uniform", 1, 60), 8, 1, 64, 64, sigma_qkv=1.0)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    sv.spec_set_tuning("attn_plan", 1)
+    try:
+        step = _step(b, cfg)
+        out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
+        torch.cuda.synchronize()
+    finally:
+        sv.spec_set_tuning("attn_plan", 0)
+    _close(out.float().cpu().numpy(), _oracle_attn(oracle, b), "many requests", sharp=True)
+    assert int(step.status.cpu()) == 0
+
+
 # --------------------------------------------------------------------------- BASELINE configurations at full size
 def _sampled_logits_check(oracle, b, gl, n_cols=192, seed=0):
     """LM head at full size: the oracle recomputes all rows for a random sample of vocabulary entries
