@@ -21,6 +21,7 @@ constexpr int kSeg = 4096;          // logits per segment
 constexpr int kThreads = 256;
 constexpr int kPerThread = kSeg / kThreads;   // 16
 constexpr int kMaxRows = 64;        // gamma_max + 1 <= 64
+constexpr int kPickLds = 512;       // segment sums staged in LDS by the pick kernel (V <= 2M entries)
 
 struct AcceptWorkspace {
     float* seg_max;      // [M, nseg]
@@ -120,6 +121,57 @@ __device__ inline void load_strided(const float* __restrict__ row, int v0, int v
     }
 }
 
+// ---- exp for the bulk sums ---------------------------------------------------------------------
+// exp(x), x <= 0, for the ~V values per row that enter Z and the residual: x = (64 m + j) ln2/64 + r with
+// |r| <= ln2/128, exp(x) = 2^m * 2^(j/64) * (1 + r + ... + r^5/120).  The 64 table values are correctly rounded;
+// the reduction constant is split so that n * hi is exact.  Relative error <= 3.3e-16 (checked against 60-digit
+// arithmetic on 2e5 arguments), about 20 issue slots instead of the ~46 of the library routine.  Single compared
+// values (the accept test) still use the library exp.
+__device__ const double kExp2Tbl[64] = {
+    1.0, 1.0108892860517005, 1.0218971486541166, 1.0330248790212284,
+    1.0442737824274138, 1.0556451783605572, 1.0671404006768237, 1.0787607977571199,
+    1.0905077326652577, 1.102382583307841, 1.1143867425958924, 1.1265216186082418,
+    1.1387886347566916, 1.1511892299529827, 1.1637248587775775, 1.1763969916502812,
+    1.189207115002721, 1.202156731452703, 1.215247359980469, 1.22848053610687,
+    1.241857812073484, 1.255380757024691, 1.2690509571917332, 1.2828700160787783,
+    1.2968395546510096, 1.3109612115247644, 1.3252366431597413, 1.339667524053303,
+    1.3542555469368927, 1.3690024229745905, 1.383909881963832, 1.3989796725383112,
+    1.4142135623730951, 1.42961333839197, 1.4451808069770467, 1.460917794180647,
+    1.4768261459394993, 1.4929077282912648, 1.5091644275934228, 1.5255981507445384,
+    1.5422108254079407, 1.559004400237837, 1.5759808451078865, 1.593142151342267,
+    1.6104903319492543, 1.6280274218573478, 1.645755478153965, 1.6636765803267364,
+    1.681792830507429, 1.7001063537185235, 1.718619298122478, 1.7373338352737062,
+    1.7562521603732995, 1.7753764925265212, 1.7947090750031072, 1.8142521755003989,
+    1.8340080864093424, 1.8539791250833855, 1.8741676341103, 1.8945759815869656,
+    1.9152065613971474, 1.9360617934922943, 1.9571441241754002, 1.978456026387951
+};
+
+__device__ inline void load_exp_table(double* s_tbl, int tid)
+{
+    if (tid < 64) s_tbl[tid] = kExp2Tbl[tid];
+}
+
+__device__ inline double exp_bulk(double x, const double* s_tbl)
+{
+    // Below -700 the true value (< 1e-304) cannot change a sum that holds a term >= 1 nor survive the
+    // rounding of a probability to fp32, so the argument is clamped there: the result then stays a normal
+    // number and 2^m can be applied by adding m to the exponent field.  -inf (a masked entry) ends here too.
+    x = fmax(x, -700.0);
+    const double kMagic = 6755399441055744.0;             // 1.5 * 2^52: the sum's low mantissa bits are rint(.)
+    const double t = fma(x, 92.33248261689366, kMagic);   // 64 / ln 2
+    const int n = __double2loint(t);
+    const double nd = t - kMagic;
+    double r = fma(nd, -0.01083042469326756, x);          // ln2/64, high part (21 trailing zero bits)
+    r = fma(nd, -2.9815858269852933e-12, r);              // ln2/64, low part
+    double q = fma(r, 1.0 / 120.0, 1.0 / 24.0);
+    q = fma(r, q, 1.0 / 6.0);
+    q = fma(r, q, 0.5);
+    q = fma(r, q, 1.0);
+    q = fma(r, q, 1.0);
+    const double v = s_tbl[n & 63] * q;                   // in (0.99, 2.02)
+    return __hiloint2double(__double2hiint(v) + ((n >> 6) << 20), __double2loint(v));
+}
+
 // ---- 1. per-segment statistics ---------------------------------------------------------------
 constexpr int kSegPerWg = 1;        // consecutive segments one workgroup handles (all loads issued up front)
 
@@ -132,7 +184,9 @@ __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
     __shared__ int s_a[kSegPerWg][kThreads / 64];
     __shared__ int s_bad[kSegPerWg][kThreads / 64];
     __shared__ double s_z[kSegPerWg][kThreads / 64];
+    __shared__ double s_tbl[64];
     const int seg0 = blockIdx.x * kSegPerWg, row = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    load_exp_table(s_tbl, tid);                           // visible after the barrier below
     if (stats && blockIdx.x == 0 && row == 0 && tid < 4) stats[tid] = (tid == 2) ? B : 0;
     const float* lrow = logits + (size_t)row * V;
     float x[kSegPerWg][kPerThread];
@@ -180,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
             if (!bb[q] && bm[q] > -INFINITY && bm[q] < INFINITY) {
                 const double dm = (double)bm[q];
 #pragma unroll
-                for (int k = 0; k < kPerThread; ++k) z += exp(((double)x[q][k] - dm) * inv_t);
+                for (int k = 0; k < kPerThread; ++k) z += exp_bulk(((double)x[q][k] - dm) * inv_t, s_tbl);
             }
             z = wave_sum(z);
             if (lane == 0) s_z[q][wave] = z;
@@ -270,6 +324,17 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
         }
         if (lane == 0) { s_m[j] = (double)m; s_z[j] = z; s_arg[j] = arg; s_bad[j] = bad; }
     }
+    // what the walk below needs per draft (token, its logit on the previous row, its draft probability) is
+    // fetched by gamma threads at once: one memory round trip instead of one per draft
+    __shared__ int s_tok[kMaxRows];
+    __shared__ float s_logit[kMaxRows], s_qd[kMaxRows];
+    if (tid >= 1 && tid <= gamma) {
+        const int d = tokens[r0 + tid];
+        const bool ok = d >= 0 && d < V;
+        s_tok[tid] = d;
+        s_logit[tid] = (ok && T > 0.0f) ? logits[(size_t)(r0 + tid - 1) * V + d] : 0.0f;
+        s_qd[tid] = (ok && T > 0.0f && draft_probs) ? draft_probs[(size_t)(r0 - i + tid - 1) * V + d] : 1.0f;
+    }
     __syncthreads();
     if (tid != 0) return;
 
@@ -278,7 +343,7 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
     if (T > 0.0f && seeds == nullptr) { valid = false; flags |= SPEC_FLAG_NO_SEED; }
     for (int j = 0; j <= gamma; ++j) if (s_bad[j]) { valid = false; flags |= SPEC_FLAG_BAD_LOGITS; }
     for (int j = 1; j <= gamma; ++j) {
-        const int d = tokens[r0 + j];
+        const int d = s_tok[j];
         if (d < 0 || d >= V) { valid = false; flags |= SPEC_FLAG_BAD_TOKEN; }
     }
     if (!(T >= 0.0f)) flags |= SPEC_FLAG_BAD_LOGITS;
@@ -290,16 +355,15 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
         return;
     }
     if (T == 0.0f) {
-        while (a < gamma && tokens[r0 + a + 1] == s_arg[a]) ++a;
+        while (a < gamma && s_tok[a + 1] == s_arg[a]) ++a;
         emit[a] = s_arg[a];
     } else {
         const uint64_t seed = seeds[i];
         int rejected_at = 0;
         for (int j = 1; j <= gamma; ++j) {
-            const int d = tokens[r0 + j];
-            const double l = (double)logits[(size_t)(r0 + j - 1) * V + d];
+            const double l = (double)s_logit[j];
             const float p = (float)(exp((l - s_m[j - 1]) / Td) / s_z[j - 1]);
-            const float qd = draft_probs ? draft_probs[(size_t)(r0 - i + j - 1) * V + d] : 1.0f;
+            const float qd = s_qd[j];
             const float u = philox_uniform(seed, round, (uint32_t)j, 0u);
             if ((float)((double)u * (double)qd) < p) ++a;
             else { rejected_at = j; break; }
@@ -307,7 +371,7 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
         if (rejected_at) {
             w.job_row[i] = r0 + rejected_at - 1;
             w.job_qrow[i] = draft_probs ? (r0 - i + rejected_at - 1) : -1;
-            w.job_onehot[i] = draft_probs ? -1 : tokens[r0 + rejected_at];
+            w.job_onehot[i] = draft_probs ? -1 : s_tok[rejected_at];
             w.job_u[i] = philox_uniform(seed, round, (uint32_t)rejected_at, 1u);
             w.job_m[i] = s_m[rejected_at - 1];
             w.job_z[i] = s_z[rejected_at - 1];
@@ -321,7 +385,7 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
         }
         w.job_t[i] = T;
     }
-    for (int j = 0; j < a; ++j) emit[j] = tokens[r0 + j + 1];
+    for (int j = 0; j < a; ++j) emit[j] = s_tok[j + 1];
     accept_len[i] = a;
     if (rollback) rollback[i] = (uint8_t)(a < gamma);
     if (stats) {
@@ -331,9 +395,9 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
 }
 
 // residual weight of vocabulary entry v on the job's row: max(0, p(v) - q(v)) in fp32, and p(v)
-__device__ inline void residual_of(float l, float qv, double m, double inv_t, double z, float& p, float& rho)
+__device__ inline void residual_of(float l, float qv, double m, double inv_t, double z, const double* s_tbl, float& p, float& rho)
 {
-    p = (float)(exp(((double)l - m) * inv_t) / z);
+    p = (float)(exp_bulk(((double)l - m) * inv_t, s_tbl) / z);
     const float diff = p - qv;
     rho = diff > 0.0f ? diff : 0.0f;
 }
@@ -344,9 +408,12 @@ __global__ __launch_bounds__(kThreads) void accept_residual_sums_kernel(
     AcceptWorkspace w)
 {
     __shared__ double s_r[kThreads / 64], s_p[kThreads / 64];
+    __shared__ double s_tbl[64];
     const int seg = blockIdx.x, i = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row = w.job_row[i];
     if (row < 0) return;
+    load_exp_table(s_tbl, tid);
+    __syncthreads();
     const int qrow = w.job_qrow[i], onehot = w.job_onehot[i];
     const double m = w.job_m[i], z = w.job_z[i], inv_t = 1.0 / (double)w.job_t[i];
     const int v0 = seg * kSeg, vend = min(V, v0 + kSeg);
@@ -364,7 +431,7 @@ __global__ __launch_bounds__(kThreads) void accept_residual_sums_kernel(
             if (v < vend) {
                 const float q = qrow >= 0 ? qv[it * 4 + k] : (v == onehot ? 1.0f : 0.0f);
                 float p, rho;
-                residual_of(x[it * 4 + k], q, m, inv_t, z, p, rho);
+                residual_of(x[it * 4 + k], q, m, inv_t, z, s_tbl, p, rho);
                 rs += (double)rho;
                 ps += (double)p;
             }
@@ -388,17 +455,29 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(
 {
     __shared__ int s_seg, s_use_p, s_best, s_last;
     __shared__ double s_before, s_target, s_wave[kThreads / 64];
+    __shared__ double s_tbl[64];
     const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row = w.job_row[i];
     if (row < 0) return;
+    load_exp_table(s_tbl, tid);                           // visible after the barrier below
+    // the segment sums are walked by one thread: up to kPickLds of them come to LDS in one round trip first
+    __shared__ double s_rs[kPickLds], s_ps[kPickLds];
+    const bool staged = nseg <= kPickLds;
+    if (staged) {
+        for (int s = tid; s < nseg; s += kThreads) {
+            s_rs[s] = w.res_sum[(size_t)i * nseg + s];
+            s_ps[s] = w.p_sum[(size_t)i * nseg + s];
+        }
+        __syncthreads();
+    }
     if (tid == 0) {
-        const double* rs = w.res_sum + (size_t)i * nseg;
+        const double* rs = staged ? s_rs : w.res_sum + (size_t)i * nseg;
         double total = 0.0;
         for (int s = 0; s < nseg; ++s) total += rs[s];
         int use_p = 0;
         if (!(total > 0.0)) {                  // p == q numerically: draw from p itself
             use_p = 1;
-            rs = w.p_sum + (size_t)i * nseg;
+            rs = staged ? s_ps : w.p_sum + (size_t)i * nseg;
             total = 0.0;
             for (int s = 0; s < nseg; ++s) total += rs[s];
         }
@@ -435,7 +514,7 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(
         if (v < V) {
             const float q = qptr ? qptr[v] : (v == onehot ? 1.0f : 0.0f);
             float p, r;
-            residual_of(lrow[v], q, m, inv_t, z, p, r);
+            residual_of(lrow[v], q, m, inv_t, z, s_tbl, p, r);
             rho[k] = use_p ? p : r;
             if (rho[k] > 0.0f) my_last = v;
         }
