@@ -69,8 +69,9 @@ int spec_version(void);
  * "attn_plan" = device-built balanced work list of spec_verify_attn, 0 = automatic, 1 = always (B <= 1024),
  * 2 = never; "attn_plan_waves" = work items per CU that list aims at, 0 = automatic;
  * "lm_kernel" = kernel used by spec_lm_head, 0 = automatic (weight-streaming kernel for M <= 160, MFMA-bound
- * kernel above), 1 = weight-streaming, 2 = MFMA-bound, 3 = plain tiled, 4..7 = weight-streaming variants
- * (wave count / register-ring depth).  A forced kernel that cannot take the shape falls back to the plain
+ * kernel above), 1 = weight-streaming, 2 = MFMA-bound with direct global->LDS loads, 3 = plain tiled,
+ * 4..7 = weight-streaming variants (wave count / register-ring depth), 8 = MFMA-bound with register staging;
+ * "lm_big_waves" = waves per workgroup of the MFMA-bound kernels, 4 or 8 (default).  A forced kernel that cannot take the shape falls back to the plain
  * tiled one.  Unknown key: SPEC_EINVAL. */
 int spec_set_tuning(const char* key, int value);
 

@@ -14,6 +14,7 @@ char* error_buffer()
 
 extern int g_attn_chunk_override;
 extern int g_lm_kernel;
+extern int g_lm_kernel_waves;
 extern int g_attn_plan;
 extern int g_attn_plan_waves;
 
@@ -26,12 +27,14 @@ extern "C" int spec_version(void) { return 1000; }
 // Benchmark hook, not part of the numerical contract: overrides launch heuristics.
 //   "attn_chunk"  keys per kv split of spec_verify_attn (0 = automatic)
 //   "lm_kernel"   kernel used by spec_lm_head (0 = automatic)
+//   "lm_big_waves"  waves per workgroup of its MFMA-bound kernels (4 or 8)
 //   "attn_plan"   balanced work list of spec_verify_attn: 0 = automatic, 1 = always, 2 = never
 //   "attn_plan_waves"  work items per CU the list aims at (0 = automatic)
 extern "C" int spec_set_tuning(const char* key, int value)
 {
     if (key && std::strcmp(key, "attn_chunk") == 0) { specv::g_attn_chunk_override = value; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_kernel") == 0) { specv::g_lm_kernel = value; return SPEC_OK; }
+    if (key && std::strcmp(key, "lm_big_waves") == 0) { specv::g_lm_kernel_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_plan") == 0) { specv::g_attn_plan = value; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_plan_waves") == 0) { specv::g_attn_plan_waves = value; return SPEC_OK; }
     return specv::fail(SPEC_EINVAL, "spec_set_tuning: unknown key '%s'", key ? key : "(null)");

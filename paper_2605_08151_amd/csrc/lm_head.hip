@@ -369,8 +369,10 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
 // ------------------------------------------------------------------------------------------------
 constexpr int kBigBN = 256, kBigBK = 32, kBigStages = 4;
 
-template <int TMW>
-__global__ __launch_bounds__(256, 1) void lm_head_big_kernel(
+// NW = 4: waves in a 2 x 2 grid, TMW x 4 tiles each; NW = 8: 2 x 4 grid, TMW x 2 tiles each, two waves per SIMD
+// (<= 256 registers), so that one wave's barrier and LDS waits are covered by the other's MFMAs.
+template <int TMW, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void lm_head_big_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
     int M, int H, int V, int tiles_m, int tiles_n)
 {
@@ -378,12 +380,15 @@ __global__ __launch_bounds__(256, 1) void lm_head_big_kernel(
     constexpr int kRowB = kBigBK * 2;                     // 64 bytes per LDS row
     constexpr int kRows = BM + kBigBN;
     constexpr int kStage = kRows * kRowB;                 // bytes per stage
-    constexpr int kDma = kRows / 16 / 4;                  // direct loads per wave per stage (16 rows each)
+    constexpr int kGroups = kRows / 16;                   // 16-row groups of a stage
+    constexpr int kDma = (kGroups + NW - 1) / NW;         // direct loads per wave per stage; when the groups do not
+                                                          // divide evenly the surplus loads repeat the last group
+    constexpr int TNW = 16 / NW;                          // 32-wide vocabulary tiles per wave
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / (NW / 2), wn = wave % (NW / 2);
     // blockIdx -> (row tile, vocabulary tile): consecutive workgroups of one XCD walk the row tiles of one vocabulary tile
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int bn = (slot / tiles_m) * 8 + xcd, bm = slot % tiles_m;
@@ -396,7 +401,7 @@ __global__ __launch_bounds__(256, 1) void lm_head_big_kernel(
     const uint16_t* src[kDma];
 #pragma unroll
     for (int j = 0; j < kDma; ++j) {
-        const int row = 16 * (4 * j + wave) + (lane >> 2);
+        const int row = 16 * min(NW * j + wave, kGroups - 1) + (lane >> 2);
         const int ch = (lane & 3) ^ (((row >> 1) & 1) * 2 + ((row >> 2) & 1));
         // rows past M or V read the last valid row: their results are never stored
         src[j] = row < BM ? A + (size_t)min(m0 + row, M - 1) * H + ch * 8
@@ -404,14 +409,14 @@ __global__ __launch_bounds__(256, 1) void lm_head_big_kernel(
     }
     auto issue = [&](int k0, unsigned char* stage) {
 #pragma unroll
-        for (int j = 0; j < kDma; ++j) lds_dma16(src[j] + k0, stage + 16 * (4 * j + wave) * kRowB);
+        for (int j = 0; j < kDma; ++j) lds_dma16(src[j] + k0, stage + 16 * min(NW * j + wave, kGroups - 1) * kRowB);
     };
 
-    f32x16 acc[TMW][4];
+    f32x16 acc[TMW][TNW];
 #pragma unroll
     for (int i = 0; i < TMW; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TNW; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
@@ -429,22 +434,22 @@ __global__ __launch_bounds__(256, 1) void lm_head_big_kernel(
         __syncthreads();                                  // everyone's part of slab s is in LDS, slab s-1 is consumed
         if (s + kBigStages - 1 < nslab) issue((s + kBigStages - 1) * kBigBK, smem + ((s + kBigStages - 1) % kBigStages) * kStage);
         const unsigned char* sa = cur + (wm * (BM / 2) + r32) * kRowB;
-        const unsigned char* sb = cur + (BM + wn * 128 + r32) * kRowB;
-        bf16x8 fa[2][TMW], fb[2][4];
+        const unsigned char* sb = cur + (BM + wn * (32 * TNW) + r32) * kRowB;
+        bf16x8 fa[2][TMW], fb[2][TNW];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const int off = ((ks * 2 + kg) ^ swz) << 4;
 #pragma unroll
             for (int i = 0; i < TMW; ++i) fa[ks][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * kRowB + off);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) fb[ks][j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * kRowB + off);
+            for (int j = 0; j < TNW; ++j) fb[ks][j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * kRowB + off);
         }
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int i = 0; i < TMW; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < TNW; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
     }
     // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.  The four
@@ -456,32 +461,176 @@ __global__ __launch_bounds__(256, 1) void lm_head_big_kernel(
         for (int r = 0; r < 16; ++r) {
             const int gr = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int gc = n0 + wn * 128 + j * 32 + r32;
+            for (int j = 0; j < TNW; ++j) {
+                const int gc = n0 + wn * (32 * TNW) + j * 32 + r32;
                 if (gr < M && gc < V) C[(size_t)gr * V + gc] = acc[i][j][r];
             }
         }
 }
 
-template <int TMW>
+template <int TMW, int NW>
 static int launch_big(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
 {
     constexpr int BM = 64 * TMW;
     const size_t smem = (size_t)kBigStages * (BM + kBigBN) * kBigBK * 2;
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_big_kernel<TMW>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_big_kernel<TMW, NW>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
         configured = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (V + kBigBN - 1) / kBigBN;
     const long grid = (long)((tiles_n + 7) / 8) * 8 * tiles_m;
-    hipLaunchKernelGGL(lm_head_big_kernel<TMW>, dim3((unsigned)grid), dim3(256), smem, s, a, w, c, M, H, V, tiles_m, tiles_n);
+    hipLaunchKernelGGL((lm_head_big_kernel<TMW, NW>), dim3((unsigned)grid), dim3(64 * NW), smem, s, a, w, c, M, H, V, tiles_m, tiles_n);
     return SPEC_OK;
 }
 
-int g_lm_kernel = 0;   // benchmark hook: 0 = automatic, 1 = weight-streaming, 2 = MFMA-bound, 3 = plain tiled,
+// ------------------------------------------------------------------------------------------------
+// MFMA-bound kernel, second form: operands travel L2 -> registers -> LDS in slabs of 64 k.
+//   Plain 16-byte register loads with 128 contiguous bytes per row and instruction deliver ~17.5 TB/s into the
+//   CUs against ~12.5 TB/s for the direct loads above (measured with the math removed).
+//   * Same tile, XCD-aware tile order and wave grids as above; LDS holds 2 stages of (BM + 256) rows x 128 B,
+//     16-byte chunks XOR-swizzled by row (chunk ^ row%8): conflict-free for the 8-lanes-per-row stores and for
+//     the 8-rows-per-phase fragment reads.
+//   * Two slabs are in flight in registers while one is multiplied: slab s+1 is written to the idle stage in the
+//     middle of iteration s and its registers immediately take slab s+3.  One barrier per slab.
+//   Measured on MI355X (V = 151936, H = 4096; M = 576 / 1152): direct loads 943 / 1665 us with 4 waves and
+//   957 / 1683 us with 8; this kernel 948 / 1670 us with 4 waves and 900 / 1592 us with 8, the default.  With the
+//   chip power-limited to ~1.5 PFLOP/s under random bf16 data the MFMAs alone take ~930 us at M = 1152.
+// ------------------------------------------------------------------------------------------------
+constexpr int kB2BK = 64;
+
+template <int TMW, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void lm_head_big2_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ W, float* __restrict__ C,
+    int M, int H, int V, int tiles_m, int tiles_n)
+{
+    constexpr int BM = 64 * TMW;
+    constexpr int kRowB = kB2BK * 2;                      // 128 bytes per LDS row
+    constexpr int kRows = BM + kBigBN;
+    constexpr int kStage = kRows * kRowB;
+    constexpr int kGroups = kRows / 8;                    // 8-row groups of a slab
+    constexpr int kLd = (kGroups + NW - 1) / NW;          // loads per wave per slab; surplus loads repeat the last group
+    constexpr int TNW = 16 / NW;                          // 32-wide vocabulary tiles per wave
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / (NW / 2), wn = wave % (NW / 2);
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int bn = (slot / tiles_m) * 8 + xcd, bm = slot % tiles_m;
+    if (bn >= tiles_n) return;
+    const int m0 = bm * BM, n0 = bn * kBigBN;
+
+    // loader role: instruction j of this wave moves 8 rows of the slab (rows 0..BM-1 = hidden, BM.. = W);
+    // lane -> (row = lane/8, 16-byte chunk = lane%8)
+    const int lr = lane >> 3, lc = lane & 7;
+    const uint16_t* src[kLd];
+    int dst[kLd];
+#pragma unroll
+    for (int j = 0; j < kLd; ++j) {
+        const int row = 8 * min(NW * j + wave, kGroups - 1) + lr;
+        // rows past M or V read the last valid row: their results are never stored
+        src[j] = row < BM ? A + (size_t)min(m0 + row, M - 1) * H + lc * 8
+                          : W + (size_t)min(n0 + row - BM, V - 1) * H + lc * 8;
+        dst[j] = row * kRowB + ((lc ^ lr) << 4);
+    }
+    u32x4 stg[2][kLd];
+    auto fetch = [&](int set, int k0) {
+#pragma unroll
+        for (int j = 0; j < kLd; ++j) stg[set][j] = *reinterpret_cast<const u32x4*>(src[j] + k0);
+    };
+    auto stash = [&](int set, unsigned char* stage) {
+#pragma unroll
+        for (int j = 0; j < kLd; ++j) *reinterpret_cast<u32x4*>(stage + dst[j]) = stg[set][j];
+    };
+
+    f32x16 acc[TMW][TNW];
+#pragma unroll
+    for (int i = 0; i < TMW; ++i)
+#pragma unroll
+        for (int j = 0; j < TNW; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    const int r32 = lane & 31, kg = lane >> 5;
+    const int sa_off = (wm * (BM / 2) + r32) * kRowB, sb_off = (BM + wn * (32 * TNW) + r32) * kRowB;
+    const int nslab = H / kB2BK;                          // >= 2 and even (H % 128 == 0)
+    unsigned char* st0 = smem;
+    unsigned char* st1 = smem + kStage;
+    fetch(0, 0);
+    fetch(1, kB2BK);
+    stash(0, st0);
+    fetch(0, min(2 * kB2BK, H - kB2BK));
+    __syncthreads();
+    for (int s2 = 0; s2 < nslab; s2 += 2) {
+#pragma unroll
+        for (int par = 0; par < 2; ++par) {
+            const int s = s2 + par;
+            const unsigned char* cur = par ? st1 : st0;
+            unsigned char* oth = par ? st0 : st1;         // held slab s-1, consumed before the last barrier
+            bf16x8 fa[2][TMW], fb[2][TNW];
+            auto read_frags = [&](int buf, int ks) {
+                const int off = ((ks * 2 + kg) ^ (r32 & 7)) << 4;
+#pragma unroll
+                for (int i = 0; i < TMW; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(cur + sa_off + i * 32 * kRowB + off);
+#pragma unroll
+                for (int j = 0; j < TNW; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(cur + sb_off + j * 32 * kRowB + off);
+            };
+            read_frags(0, 0);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks < 3) read_frags((ks + 1) & 1, ks + 1);
+#pragma unroll
+                for (int i = 0; i < TMW; ++i)
+#pragma unroll
+                    for (int j = 0; j < TNW; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+                if (ks == 1) {
+                    // slab s+1 (requested two iterations ago) goes to the idle stage; its registers take slab s+3
+                    // (past the end: a valid slab again, never stashed)
+                    if (s + 1 < nslab) stash(par ^ 1, oth);
+                    fetch(par ^ 1, min((s + 3) * kB2BK, H - kB2BK));
+                }
+            }
+            __syncthreads();                              // slab s is consumed, slab s+1 is in LDS
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TMW; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int gr = m0 + wm * (BM / 2) + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+#pragma unroll
+            for (int j = 0; j < TNW; ++j) {
+                const int gc = n0 + wn * (32 * TNW) + j * 32 + r32;
+                if (gr < M && gc < V) C[(size_t)gr * V + gc] = acc[i][j][r];
+            }
+        }
+}
+
+template <int TMW, int NW>
+static int launch_big2(const uint16_t* a, const uint16_t* w, float* c, int M, int H, int V, hipStream_t s)
+{
+    constexpr int BM = 64 * TMW;
+    const size_t smem = 2 * (size_t)(BM + kBigBN) * kB2BK * 2;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_big2_kernel<TMW, NW>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
+        configured = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (V + kBigBN - 1) / kBigBN;
+    const long grid = (long)((tiles_n + 7) / 8) * 8 * tiles_m;
+    hipLaunchKernelGGL((lm_head_big2_kernel<TMW, NW>), dim3((unsigned)grid), dim3(64 * NW), smem, s, a, w, c, M, H, V, tiles_m, tiles_n);
+    return SPEC_OK;
+}
+
+int g_lm_kernel_waves = 8;  // benchmark hook: waves per workgroup of the MFMA-bound kernel (4 or 8)
+int g_lm_kernel = 0;   // benchmark hook: 0 = automatic, 1 = weight-streaming, 2 = MFMA-bound with direct loads, 3 = plain tiled,
+                       // 8 = MFMA-bound with register staging (the automatic choice for M > 160),
                        // 4 = weight-streaming with 8 waves (4 x 2) and a 2-slab ring, 5/6/7 = 4 waves with
                        // 2-slab ring / 4-slab ring + paired refills / 2-slab ring + paired refills (the default)
 
@@ -605,10 +754,18 @@ extern "C" int spec_lm_head(const void* hidden, const void* W, float* logits, in
         else if (M <= 128) rc = launch_skinny_auto<8>(a, w, logits, M, H, V, s);
         else rc = launch_skinny_auto<10>(a, w, logits, M, H, V, s);
         if (rc != SPEC_OK) return rc;
-    } else if ((force == 2 || (force == 0 && M > 160)) && H % kBigBK == 0 && H >= kBigBK * kBigStages) {
+    } else if ((force == 8 || (force == 0 && M > 160)) && H % (2 * kB2BK) == 0) {
+        const int waste192 = (M + 191) / 192 * 192 - M, waste256 = (M + 255) / 256 * 256 - M;
+        int rc;
+        if (g_lm_kernel_waves == 4) rc = waste192 <= waste256 ? launch_big2<3, 4>(a, w, logits, M, H, V, s) : launch_big2<4, 4>(a, w, logits, M, H, V, s);
+        else rc = waste192 <= waste256 ? launch_big2<3, 8>(a, w, logits, M, H, V, s) : launch_big2<4, 8>(a, w, logits, M, H, V, s);
+        if (rc != SPEC_OK) return rc;
+    } else if ((force == 2 || (force == 0 && M > 160)) && H % kBigBK == 0 && H >= kBigBK * kBigStages) {   // H % 128 != 0 ends here
         // row tiles of 192 or 256: whichever wastes fewer padded rows
         const int waste192 = (M + 191) / 192 * 192 - M, waste256 = (M + 255) / 256 * 256 - M;
-        const int rc = waste192 <= waste256 ? launch_big<3>(a, w, logits, M, H, V, s) : launch_big<4>(a, w, logits, M, H, V, s);
+        int rc;
+        if (g_lm_kernel_waves == 4) rc = waste192 <= waste256 ? launch_big<3, 4>(a, w, logits, M, H, V, s) : launch_big<4, 4>(a, w, logits, M, H, V, s);
+        else rc = waste192 <= waste256 ? launch_big<3, 8>(a, w, logits, M, H, V, s) : launch_big<4, 8>(a, w, logits, M, H, V, s);
         if (rc != SPEC_OK) return rc;
     } else if (M <= 64) {
         const long tiles = (long)((M + 63) / 64) * ((V + 127) / 128);
