@@ -586,6 +586,60 @@ def test_attention_with_more_requests_than_the_work_list_takes(sv, oracle):
     assert int(step.status.cpu()) == 0
 
 
+def test_step_can_be_captured_in_a_graph_and_replayed(sv, oracle):
+    """The four calls never allocate or synchronise, so a stream capture takes them; three replays, with eager
+    work and synchronisations in between, reproduce the eager step bit for bit (work-list attention included)."""
+    cfg = wl.VerifyConfig("graph", 51, 12, (0, 2, 4), ("uniform", 200, 2500), 8, 1, 512, 9001,
+                          temperature=("alternate", 0.0, 0.9), sigma_qkv=1.0)
+    b = wl.make_batch(cfg, device="cuda")
+    qo = b["qo_indptr"]
+    sv.spec_set_tuning("attn_plan", 1)
+    try:
+        step = _step(b, cfg)
+        logits = step.lm_head(b["hidden"], b["W"])
+        torch.cuda.synchronize()
+        dp, tokens = wl.draft_probs_noisy(cfg, qo, logits)
+        tokens = tokens.cuda()
+        pristine = (b["page_table"].clone(), b["seq_lens"].clone(), b["free_list"].clone(), b["free_count"].clone())
+        pt, sl, fl, fc = [t.clone() for t in pristine]
+
+        def one():
+            for dst, src in zip((pt, sl, fl, fc), pristine):
+                dst.copy_(src)
+            step.attn(b["q"], b["k_cache"], b["v_cache"], pt, sl, qo, b["scale"])
+            step.lm_head(b["hidden"], b["W"])
+            step.accept(tokens, dp, b["temperature"], b["seeds"], 2, qo)
+            step.commit(pt, sl, qo, fl, fc, cfg.P)
+
+        one()
+        torch.cuda.synchronize()
+        outputs = lambda: (step.attn_out, step.lse, step.logits, step.accept_len, step.out_tokens, step.rollback,
+                           step.stats, pt, sl, fl, fc)
+        ref = [t.clone() for t in outputs()]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            one()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            step.accept_len.fill_(-5)
+            step.logits.zero_()
+            step.attn_out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            for x, y in zip(outputs(), ref):
+                assert torch.equal(x, y)
+            one()                                        # eager work between the replays
+            torch.cuda.synchronize()
+        assert int(step.status.cpu()) == 0
+    finally:
+        sv.spec_set_tuning("attn_plan", 0)
+
+
 # --------------------------------------------------------------------------- BASELINE configurations at full size
 def _sampled_logits_check(oracle, b, gl, n_cols=192, seed=0):
     """LM head at full size: the oracle recomputes all rows for a random sample of vocabulary entries
