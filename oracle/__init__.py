@@ -154,3 +154,28 @@ def next_mode(rollback_count, emitted, B, gamma, T_D, T_T):
     mode = _load().oracle_next_mode(int(rollback_count), int(emitted), int(B), float(gamma), float(T_D), float(T_T),
                                     ctypes.byref(rh), ctypes.byref(rs))
     return int(mode), rh.value, rs.value
+
+
+def assemble_next(accept_len, out_tokens, qo_indptr, cont, cont_len, repair, repair_len, mode, gamma_next):
+    """Candidates of the next round (Method, eqs. ordinary_* / parallel_*; Appendix, eq. target_suffix_reuse).
+    cont / repair: int32 [B, C] / [B, R] with per-request lengths, or None.  Returns a dict."""
+    lib = _load()
+    B = accept_len.shape[0]
+    gamma_max = out_tokens.shape[1] - 1
+    nt = np.full(B * (gamma_next + 1), -7, np.int32)
+    nqo = np.zeros(B + 1, np.int32)
+    rb = np.zeros(B, np.uint8)
+    st = np.zeros(4, np.int32)
+    null = ctypes.c_void_p(None)
+    lib.oracle_assemble_next.restype = ctypes.c_int
+    rows = lib.oracle_assemble_next(
+        _p(accept_len, np.int32), _p(out_tokens, np.int32), ctypes.c_int(gamma_max), _p(qo_indptr, np.int32), ctypes.c_int(B),
+        _p(cont, np.int32) if cont is not None else null, ctypes.c_int(cont.shape[1] if cont is not None else 0),
+        _p(cont_len, np.int32) if cont is not None else null,
+        _p(repair, np.int32) if repair is not None else null, ctypes.c_int(repair.shape[1] if repair is not None else 0),
+        _p(repair_len, np.int32) if repair is not None else null,
+        ctypes.c_int(mode), ctypes.c_int(gamma_next), _p(nt, np.int32), _p(nqo, np.int32),
+        rb.ctypes.data_as(ctypes.c_void_p), _p(st, np.int32))
+    _check(min(rows, 0), "oracle_assemble_next")
+    return dict(tokens=nt[:rows].copy(), qo_indptr=nqo, rollback=rb, stats=st, rows=rows)
+

@@ -377,3 +377,71 @@ int oracle_next_mode(int rollback_count, int emitted, int B, double gamma, doubl
     if (r_star_out) *r_star_out = rs;
     return r_hat <= rs ? 1 : 0;
 }
+
+/* ------------------------------------------------------------------------- *
+ * Candidates of round n+1 (Method, "Execution in ordinary mode" / "Execution in
+ * parallel mode", eqs. ordinary_rollback_seq, ordinary_stable_seq,
+ * parallel_stable_seq, parallel_rollback_pad; Appendix "Target side",
+ * eq. target_suffix_reuse).  Per request, after round n: a = accepted drafts,
+ * b = bonus token (out_tokens[i][a]), gamma_i = drafts that were verified.
+ *   cont[i][0 .. cont_len[i])   the continuation the drafter prepared while round n
+ *                               was verified: what it expects AFTER the verified
+ *                               drafts; its first token is its guess of b.
+ *   repair[i][0 .. repair_len[i])  ordinary mode only: the continuation regenerated
+ *                               from b for a rollback request.
+ * A request is stable iff all its drafts were accepted and the prepared
+ * continuation agrees with what the target committed, i.e. cont_len >= 1 and
+ * cont[0] == b (the reading taken for Consistent()); otherwise it is in the
+ * rollback set: "its speculative prefix is rejected ... or its previously
+ * prepared draft continuation is invalidated by the verification result".
+ *   stable:              y = [b, cont[1 .. 1+g)]           g = min(cont_len-1, gamma_next)
+ *   rollback, ORDINARY:  y = [b, repair[0 .. g)]           g = min(repair_len, gamma_next)
+ *   rollback, PARALLEL:  y = [b]                           (the padded candidate, ragged)
+ * A request whose acceptance failed (bonus < 0) gets the single row [-1].
+ * Writes next_tokens (rows of all requests, request order), next_qo_indptr [B+1],
+ * rollback [B], stats = {|R_n|, sum (a+1), B, rows of round n+1}.
+ * mode: 0 = ORDINARY, 1 = PARALLEL.  Returns the number of rows, or < 0.
+ * ------------------------------------------------------------------------- */
+int oracle_assemble_next(const int32_t* accept_len, const int32_t* out_tokens, int gamma_max,
+                         const int32_t* qo_indptr, int B,
+                         const int32_t* cont, int cont_stride, const int32_t* cont_len,
+                         const int32_t* repair, int repair_stride, const int32_t* repair_len,
+                         int mode, int gamma_next,
+                         int32_t* next_tokens, int32_t* next_qo_indptr, uint8_t* rollback, int32_t* stats)
+{
+    if (!accept_len || !out_tokens || !qo_indptr || !next_tokens || !next_qo_indptr) return ORACLE_EINVAL;
+    if (B < 0 || gamma_max < 0 || gamma_next < 0 || (mode != 0 && mode != 1)) return ORACLE_EINVAL;
+    int rows = 0, rolled = 0, emitted = 0;
+    next_qo_indptr[0] = 0;
+    for (int i = 0; i < B; ++i) {
+        const int gamma = qo_indptr[i + 1] - qo_indptr[i] - 1;
+        const int a = accept_len[i];
+        const int ok = gamma >= 0 && gamma <= gamma_max && a >= 0 && a <= gamma;
+        const int b = ok ? out_tokens[(size_t)i * (gamma_max + 1) + a] : -1;
+        int is_rollback = 1, g = 0;
+        const int32_t* from = NULL;
+        if (b >= 0) {
+            const int cl = (cont && cont_len) ? cont_len[i] : 0;
+            if (a == gamma && cl >= 1 && cont[(size_t)i * cont_stride] == b) {
+                is_rollback = 0;
+                g = cl - 1 < gamma_next ? cl - 1 : gamma_next;
+                from = cont + (size_t)i * cont_stride + 1;
+            } else if (mode == 0 && repair && repair_len) {
+                g = repair_len[i] < gamma_next ? repair_len[i] : gamma_next;
+                if (g < 0) g = 0;
+                from = repair + (size_t)i * repair_stride;
+            }
+            emitted += a + 1;
+        } else {
+            is_rollback = gamma > 0;          /* what spec_accept reports for a request it could not decide */
+        }
+        next_tokens[rows++] = b;
+        for (int j = 0; j < g; ++j) next_tokens[rows++] = from[j];
+        next_qo_indptr[i + 1] = rows;
+        if (rollback) rollback[i] = (uint8_t)is_rollback;
+        rolled += is_rollback;
+    }
+    if (stats) { stats[0] = rolled; stats[1] = emitted; stats[2] = B; stats[3] = rows; }
+    return rows;
+}
+
