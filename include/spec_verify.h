@@ -231,6 +231,42 @@ int spec_kv_commit(int32_t* page_table, int max_pages_per_seq, int32_t* seq_lens
                    int32_t* free_list, int32_t free_capacity, int32_t* free_count,
                    int B, int page_size, int32_t* status_flags, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * spec_assemble_next — the candidates y_{n+1} of the next verification round,
+ * on the device, from the outputs of spec_accept (Method, "Execution in
+ * ordinary mode" and "Execution in parallel mode": eqs. ordinary_rollback_seq,
+ * ordinary_stable_seq, parallel_stable_seq, parallel_rollback_pad; Appendix
+ * "Target side", eq. target_suffix_reuse).  Per request, with a accepted
+ * drafts, bonus b = out_tokens[i][a] and gamma_i verified drafts:
+ *   stable  <=>  a == gamma_i and the continuation the drafter prepared
+ *     meanwhile starts with b (cont_len[i] >= 1 and cont[i][0] == b; the
+ *     reading taken for Consistent()).  Candidate [b, cont[i][1 .. 1+g)],
+ *     g = min(cont_len[i] - 1, gamma_next).
+ *   otherwise the request is in the rollback set ("its speculative prefix is
+ *     rejected ... or its previously prepared draft continuation is
+ *     invalidated", Method, "Rollback-Based Mode Selection"):
+ *     mode SPEC_MODE_ORDINARY with repair != NULL: [b, repair[i][0 .. g)],
+ *       g = min(repair_len[i], gamma_next) (the continuation regenerated from b);
+ *     mode SPEC_MODE_PARALLEL: [b] (the padded candidate, ragged: gamma = 0).
+ *   A request spec_accept could not decide (bonus -1) gets the row [-1].
+ * Inputs (device): accept_len [B], out_tokens [B, gamma_max+1], qo_indptr [B+1]
+ *   of the round just verified; cont [B, cont_stride] / cont_len [B] and repair
+ *   [B, repair_stride] / repair_len [B] int32, each pair NULL if absent.
+ * Outputs (device, caller-owned): next_tokens [B * (gamma_next + 1)] (rows of all
+ *   requests in request order, first row of a request = b), next_qo_indptr
+ *   [B+1], rollback [B] uint8 or NULL (the rollback set as defined above),
+ *   stats [4] int32 or NULL = {|R_n|, sum (a_i + 1), B, rows of round n+1},
+ *   the input of spec_next_mode.  Deterministic layout.  Asynchronous on stream;
+ *   SPEC_EINVAL on NULL / negative arguments or an unknown mode.
+ * ------------------------------------------------------------------------- */
+int spec_assemble_next(const int32_t* accept_len, const int32_t* out_tokens, int gamma_max,
+                       const int32_t* qo_indptr, int B,
+                       const int32_t* cont, int cont_stride, const int32_t* cont_len,
+                       const int32_t* repair, int repair_stride, const int32_t* repair_len,
+                       int mode, int gamma_next,
+                       int32_t* next_tokens, int32_t* next_qo_indptr, uint8_t* rollback,
+                       int32_t* stats, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

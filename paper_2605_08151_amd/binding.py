@@ -18,7 +18,7 @@ EXPORTS = (
     "spec_last_error_string", "spec_version", "spec_set_tuning",
     "spec_verify_attn_workspace_bytes", "spec_verify_attn", "spec_lm_head",
     "spec_accept_workspace_bytes", "spec_accept", "spec_kv_commit", "spec_next_mode",
-    "spec_lm_head_stats_blocks", "spec_lm_head_stats", "spec_accept_stats",
+    "spec_lm_head_stats_blocks", "spec_lm_head_stats", "spec_accept_stats", "spec_assemble_next",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -59,6 +59,8 @@ def _load():
     lib.spec_lm_head_stats.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
     lib.spec_accept_stats.restype = i32
     lib.spec_accept_stats.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
+    lib.spec_assemble_next.restype = i32
+    lib.spec_assemble_next.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.spec_next_mode.restype = i32
     lib.spec_next_mode.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                    ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -91,6 +93,19 @@ def spec_version():
 
 
 MODE_ORDINARY, MODE_PARALLEL = 0, 1
+
+
+def spec_assemble_next(accept_len, out_tokens, qo_indptr, cont, cont_len, repair, repair_len, mode, gamma_next,
+                       next_tokens, next_qo_indptr, rollback, stats):
+    B = accept_len.shape[0]
+    gamma_max = out_tokens.shape[1] - 1
+    assert next_tokens.numel() >= B * (gamma_next + 1) and next_qo_indptr.numel() == B + 1
+    _check(_lib.spec_assemble_next(
+        _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), gamma_max, _ptr(qo_indptr, torch.int32), B,
+        _ptr(cont, torch.int32), cont.shape[1] if cont is not None else 0, _ptr(cont_len, torch.int32),
+        _ptr(repair, torch.int32), repair.shape[1] if repair is not None else 0, _ptr(repair_len, torch.int32),
+        int(mode), int(gamma_next), _ptr(next_tokens, torch.int32), _ptr(next_qo_indptr, torch.int32),
+        _ptr(rollback, torch.uint8), _ptr(stats, torch.int32), _stream()))
 
 
 def spec_next_mode(stats_host, gamma, t_draft, t_target):

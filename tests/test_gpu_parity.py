@@ -394,6 +394,87 @@ def test_empty_batch_calls_are_noops(sv):
     torch.cuda.synchronize()
 
 
+# --------------------------------------------------------------------------- candidates of the next round
+def _assemble_both(sv, oracle, al, ot, qo, cont, cl, rep, rl, mode, gn):
+    B = al.shape[0]
+    dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    nt = torch.full((max(1, B * (gn + 1)),), -9, dtype=torch.int32, device="cuda")
+    nqo = torch.full((B + 1,), -9, dtype=torch.int32, device="cuda")
+    rb = torch.full((max(1, B),), 9, dtype=torch.uint8, device="cuda")
+    st = torch.full((4,), -9, dtype=torch.int32, device="cuda")
+    sv.spec_assemble_next(dev(al), dev(ot), dev(qo), dev(cont), dev(cl), dev(rep), dev(rl), mode, gn, nt, nqo, rb[:B], st)
+    torch.cuda.synchronize()
+    ref = oracle.assemble_next(al, ot, qo, cont, cl, rep, rl, mode, gn)
+    assert np.array_equal(nqo.cpu().numpy(), ref["qo_indptr"])
+    assert np.array_equal(nt.cpu().numpy()[:ref["rows"]], ref["tokens"])
+    assert (nt.cpu().numpy()[ref["rows"]:] == -9).all()                        # nothing written past the last row
+    assert np.array_equal(rb.cpu().numpy()[:B], ref["rollback"])
+    assert np.array_equal(st.cpu().numpy(), ref["stats"])
+    return ref
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("B", [1, 7, 64, 1024, 1025, 3000])
+def test_next_round_candidates_are_bit_exact(sv, oracle, B, mode):
+    rng = np.random.default_rng(B + mode)
+    gam = rng.choice([0, 2, 4, 8], B)
+    qo = np.zeros(B + 1, np.int32)
+    qo[1:] = np.cumsum(gam + 1)
+    al = np.array([rng.integers(0, g + 1) for g in gam], np.int32)
+    ot = np.full((B, 9), -1, np.int32)
+    bonus = rng.integers(0, 1000, B).astype(np.int32)
+    ot[np.arange(B), al] = bonus
+    undecided = rng.random(B) < 0.03                                            # requests spec_accept flagged
+    ot[undecided] = -1
+    al[undecided] = 0
+    cont = rng.integers(0, 1000, (B, 10)).astype(np.int32)
+    agree = rng.random(B) < 0.6
+    cont[agree, 0] = bonus[agree]
+    cl = rng.integers(0, 11, B).astype(np.int32)
+    rep = rng.integers(1000, 2000, (B, 6)).astype(np.int32)
+    rl = rng.integers(0, 7, B).astype(np.int32)
+    for gn in (0, 4, 8):
+        _assemble_both(sv, oracle, al, ot, qo, cont, cl, rep if mode == 0 else None, rl if mode == 0 else None, mode, gn)
+    _assemble_both(sv, oracle, al, ot, qo, None, None, None, None, mode, 4)       # no drafter output at all: every request decodes
+
+
+def test_next_round_follows_acceptance_on_the_device(sv, oracle):
+    """spec_accept -> spec_assemble_next -> spec_next_mode without a host round trip in between; the rollback set now
+    counts continuations invalidated by the bonus as well (Method, "Rollback-Based Mode Selection")."""
+    V = 4097
+    rng = np.random.default_rng(5)
+    gammas = np.full(40, 4)
+    qo = _qo(gammas)
+    logits = rng.normal(0, 0.03, (qo[-1], V)).astype(np.float32)
+    cfg = wl.VerifyConfig("g", V, len(gammas), (4,), ("const", 1), 8, 1, 64, V, rho=0.8)
+    tokens, _ = wl.draft_tokens_greedy(cfg, torch.from_numpy(qo), torch.from_numpy(logits.argmax(1)))
+    got, ref = _accept_both(sv, oracle, logits, tokens.numpy(), None, np.zeros(len(gammas), np.float32), None, 0, qo, 4)
+    _assert_same(got, ref, gammas)
+    bonus = ref["out_tokens"][np.arange(len(gammas)), ref["accept_len"]]
+    cont = rng.integers(0, V, (len(gammas), 5)).astype(np.int32)
+    right = rng.random(len(gammas)) < 0.7
+    cont[right, 0] = bonus[right]                                                 # the drafter guessed the bonus
+    cl = np.full(len(gammas), 5, np.int32)
+    r = _assemble_both(sv, oracle, got["accept_len"], got["out_tokens"], qo, cont, cl, None, None, 1, 4)
+    stable = (ref["accept_len"] == gammas) & right
+    assert np.array_equal(r["rollback"], (~stable).astype(np.uint8))
+    assert r["stats"][0] >= int(ref["rollback"].sum())                            # a superset of "prefix rejected"
+    mode = sv.spec_next_mode(r["stats"], 5, 1.0, 10.0)
+    assert mode[0] == oracle.next_mode(int(r["stats"][0]), int(r["stats"][1]), len(gammas), 5, 1.0, 10.0)[0]
+
+
+def test_next_round_host_rejections(sv):
+    z = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(sv.SpecError):                  # unknown mode
+        sv.spec_assemble_next(z[:1], z[:1].view(1, 1), z[:2], None, None, None, None, 7, 4, z.clone(), z[:2].clone(), None, None)
+    with pytest.raises(sv.SpecError):                  # negative gamma_next
+        sv.spec_assemble_next(z[:1], z[:1].view(1, 1), z[:2], None, None, None, None, 1, -1, z.clone(), z[:2].clone(), None, None)
+    nqo = torch.full((1,), 5, dtype=torch.int32, device="cuda")
+    sv.spec_assemble_next(z[:0], z[:0].view(0, 1), z[:1], None, None, None, None, 1, 4, z.clone(), nqo, None, None)   # empty batch
+    torch.cuda.synchronize()
+    assert int(nqo.cpu()) == 0
+
+
 # --------------------------------------------------------------------------- whole step
 def _run_step(sv, oracle, cfg, stochastic, fused=False):
     b = wl.make_batch(cfg, device="cuda")
