@@ -179,3 +179,36 @@ def assemble_next(accept_len, out_tokens, qo_indptr, cont, cont_len, repair, rep
     _check(min(rows, 0), "oracle_assemble_next")
     return dict(tokens=nt[:rows].copy(), qo_indptr=nqo, rollback=rb, stats=st, rows=rows)
 
+
+def divergence(p_tokens, p_indptr, h_tokens, h_indptr):
+    """delta_i = first position where request i's verified prefix and the draft's own tokens differ
+    (Appendix "Draft side", "Message handling and update")."""
+    B = p_indptr.shape[0] - 1
+    delta = np.zeros(B, np.int32)
+    _check(_load().oracle_divergence(_p(p_tokens, np.int32), _p(p_indptr, np.int32), _p(h_tokens, np.int32),
+                                     _p(h_indptr, np.int32), _p(delta, np.int32), ctypes.c_int(B)), "oracle_divergence")
+    return delta
+
+
+def kv_truncate(page_table, seq_lens, keep_len, free_list, free_count, page_size):
+    """Rollback(S, delta) on the paged cache, in place (Appendix "Draft side", "State recovery")."""
+    B = seq_lens.shape[0]
+    rc = _load().oracle_kv_truncate(
+        _p(page_table, np.int32), ctypes.c_int(page_table.shape[1]), _p(seq_lens, np.int32), _p(keep_len, np.int32),
+        _p(free_list, np.int32), ctypes.c_int32(free_list.shape[0]), _p(free_count, np.int32), B, page_size)
+    _check(rc, "oracle_kv_truncate")
+
+
+def compress_prompts(tokens, indptr, p_num, p_den):
+    """E(x) of eq. token_eviction on a ragged batch; returns (out_tokens, out_indptr, kept_index)."""
+    lib = _load()
+    lib.oracle_compress_prompts.restype = ctypes.c_long
+    B = indptr.shape[0] - 1
+    out = np.full(max(1, tokens.shape[0]), -7, np.int32)
+    idx = np.full(max(1, tokens.shape[0]), -7, np.int32)
+    oip = np.zeros(B + 1, np.int32)
+    n = lib.oracle_compress_prompts(_p(tokens, np.int32), _p(indptr, np.int32), ctypes.c_int(B), ctypes.c_int(p_num),
+                                    ctypes.c_int(p_den), _p(out, np.int32), _p(oip, np.int32), _p(idx, np.int32))
+    _check(min(n, 0), "oracle_compress_prompts")
+    return out[:n].copy(), oip, idx[:n].copy()
+

@@ -445,3 +445,89 @@ int oracle_assemble_next(const int32_t* accept_len, const int32_t* out_tokens, i
     return rows;
 }
 
+/* ------------------------------------------------------------------------- *
+ * Draft-side reconciliation (Appendix "Draft side", "Message handling and
+ * update"): delta_i = min{ t : p_i[t] != h_i[t] }, the first position at which
+ * the verified prefix p_i and the draft's own decoded tokens h_i differ
+ * (0-based over the ragged rows p_indptr / h_indptr).  When one is a prefix of
+ * the other there is no such t and delta_i is the shorter length: everything
+ * the two share is kept.
+ * ------------------------------------------------------------------------- */
+int oracle_divergence(const int32_t* p_tokens, const int32_t* p_indptr, const int32_t* h_tokens,
+                      const int32_t* h_indptr, int32_t* delta, int B)
+{
+    if (!p_indptr || !h_indptr || !delta || B < 0) return ORACLE_EINVAL;
+    for (int i = 0; i < B; ++i) {
+        const int lp = p_indptr[i + 1] - p_indptr[i], lh = h_indptr[i + 1] - h_indptr[i];
+        const int n = lp < lh ? lp : lh;
+        int t = 0;
+        while (t < n && p_tokens[p_indptr[i] + t] == h_tokens[h_indptr[i] + t]) ++t;
+        delta[i] = t;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Rollback(S, delta) on the paged KV cache (Appendix "Draft side", "State
+ * recovery": rollback truncates the speculative suffix and frees the
+ * corresponding KV cache).  Request i keeps min(len_i, max(keep_len[i], 0))
+ * tokens; the pages beyond ceil(new_len / P), up to ceil(len_i / P), are unmapped
+ * and pushed on the free list, requests ascending, logical pages ascending.
+ * ------------------------------------------------------------------------- */
+int oracle_kv_truncate(int32_t* page_table, int max_pages_per_seq, int32_t* seq_lens, const int32_t* keep_len,
+                       int32_t* free_list, int32_t free_capacity, int32_t* free_count, int B, int page_size)
+{
+    if (!page_table || !seq_lens || !keep_len || !free_list || !free_count) return ORACLE_EINVAL;
+    if (B < 0 || page_size <= 0 || max_pages_per_seq < 0) return ORACLE_EINVAL;
+    int status = ORACLE_OK;
+    for (int i = 0; i < B; ++i) {
+        const int c = seq_lens[i];
+        int k = keep_len[i];
+        if (k < 0) k = 0;
+        if (k > c) k = c;
+        const int had = (c + page_size - 1) / page_size;
+        const int keep = (k + page_size - 1) / page_size;
+        for (int pg = keep; pg < had && pg < max_pages_per_seq; ++pg) {
+            int32_t* slot = page_table + (size_t)i * max_pages_per_seq + pg;
+            if (*slot >= 0) {
+                if (*free_count < free_capacity) free_list[(*free_count)++] = *slot;
+                else status = ORACLE_EINVAL;
+                *slot = -1;
+            }
+        }
+        seq_lens[i] = k;
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- *
+ * Draft-side context compression (Method, "Draft-side context compression",
+ * eq. token_eviction): E(x_{1:S}) = [x_{:k}, x_{S-k+1:}], k = floor(p S / 2),
+ * the first k and the last k tokens of a prompt, 2k <= p S of them, with the
+ * retained ratio p = p_num / p_den given as a fraction so that k is an exact
+ * integer: k = (p_num * S) / (2 * p_den).  A prompt with 2k >= S is kept whole.
+ * Ragged in (tokens, indptr [B+1]) and out; kept_index (optional) receives the
+ * position inside its prompt of every kept token.  Returns the number of
+ * tokens kept, or < 0.
+ * ------------------------------------------------------------------------- */
+long oracle_compress_prompts(const int32_t* tokens, const int32_t* indptr, int B, int p_num, int p_den,
+                             int32_t* out_tokens, int32_t* out_indptr, int32_t* kept_index)
+{
+    if (!indptr || !out_indptr || B < 0 || p_num < 0 || p_den <= 0) return ORACLE_EINVAL;
+    long n = 0;
+    out_indptr[0] = 0;
+    for (int i = 0; i < B; ++i) {
+        const long S = indptr[i + 1] - indptr[i];
+        const long k = (long)p_num * S / (2L * p_den);
+        const int32_t* x = tokens + indptr[i];
+        if (2 * k >= S) {
+            for (long t = 0; t < S; ++t) { out_tokens[n] = x[t]; if (kept_index) kept_index[n] = (int32_t)t; ++n; }
+        } else {
+            for (long t = 0; t < k; ++t) { out_tokens[n] = x[t]; if (kept_index) kept_index[n] = (int32_t)t; ++n; }
+            for (long t = S - k; t < S; ++t) { out_tokens[n] = x[t]; if (kept_index) kept_index[n] = (int32_t)t; ++n; }
+        }
+        out_indptr[i + 1] = (int32_t)n;
+    }
+    return n;
+}
+
