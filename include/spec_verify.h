@@ -267,6 +267,41 @@ int spec_assemble_next(const int32_t* accept_len, const int32_t* out_tokens, int
                        int32_t* next_tokens, int32_t* next_qo_indptr, uint8_t* rollback,
                        int32_t* stats, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Draft-side primitives (Appendix "Draft side"; Method, "Draft-side context
+ * compression").  Integer-only, ragged, asynchronous on stream; device pointers.
+ *
+ * spec_divergence — "Message handling and update": delta_i = min{ t :
+ *   p_i[t] != h_i[t] } between the verified prefix p_i and the draft's own
+ *   decoded tokens h_i (rows p_indptr[i] .. p_indptr[i+1] of p_tokens, likewise
+ *   h); when one is a prefix of the other, the shorter length.  delta [B] int32.
+ *
+ * spec_kv_truncate — "State recovery", Rollback(S, delta): request i keeps
+ *   min(seq_lens[i], max(keep_len[i], 0)) tokens; the pages beyond
+ *   ceil(new_len / page_size) are set to -1 in page_table and appended to
+ *   free_list (requests ascending, logical pages ascending), seq_lens and
+ *   *free_count are updated.  Arguments, flags and errors as spec_kv_commit.
+ *
+ * spec_compress_prompts — eq. token_eviction: E(x_{1:S}) = [x_{:k}, x_{S-k+1:}],
+ *   k = floor(p S / 2): the first k and the last k tokens, with the retained
+ *   ratio p = p_num / p_den given as a fraction (k = p_num * S / (2 p_den) in
+ *   integers; the paper's p = 0.1 is 1 / 10).  A prompt with 2k >= S is kept
+ *   whole.  tokens / indptr [B+1] in; out_tokens (capacity: the input's token
+ *   count), out_indptr [B+1], kept_index (or NULL: the position inside its
+ *   prompt of every kept token) out.
+ * SPEC_EINVAL on NULL / negative arguments; nothing is launched for B == 0
+ * except that out_indptr[0] is set.
+ * ------------------------------------------------------------------------- */
+int spec_divergence(const int32_t* p_tokens, const int32_t* p_indptr, const int32_t* h_tokens,
+                    const int32_t* h_indptr, int32_t* delta, int B, void* stream);
+
+int spec_kv_truncate(int32_t* page_table, int max_pages_per_seq, int32_t* seq_lens, const int32_t* keep_len,
+                     int32_t* free_list, int32_t free_capacity, int32_t* free_count,
+                     int B, int page_size, int32_t* status_flags, void* stream);
+
+int spec_compress_prompts(const int32_t* tokens, const int32_t* indptr, int B, int p_num, int p_den,
+                          int32_t* out_tokens, int32_t* out_indptr, int32_t* kept_index, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

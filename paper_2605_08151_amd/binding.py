@@ -19,6 +19,7 @@ EXPORTS = (
     "spec_verify_attn_workspace_bytes", "spec_verify_attn", "spec_lm_head",
     "spec_accept_workspace_bytes", "spec_accept", "spec_kv_commit", "spec_next_mode",
     "spec_lm_head_stats_blocks", "spec_lm_head_stats", "spec_accept_stats", "spec_assemble_next",
+    "spec_divergence", "spec_kv_truncate", "spec_compress_prompts",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -59,6 +60,12 @@ def _load():
     lib.spec_lm_head_stats.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
     lib.spec_accept_stats.restype = i32
     lib.spec_accept_stats.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
+    lib.spec_divergence.restype = i32
+    lib.spec_divergence.argtypes = [vp, vp, vp, vp, vp, i32, vp]
+    lib.spec_kv_truncate.restype = i32
+    lib.spec_kv_truncate.argtypes = [vp, i32, vp, vp, vp, i32, vp, i32, i32, vp, vp]
+    lib.spec_compress_prompts.restype = i32
+    lib.spec_compress_prompts.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.spec_assemble_next.restype = i32
     lib.spec_assemble_next.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.spec_next_mode.restype = i32
@@ -197,3 +204,26 @@ def spec_kv_commit(page_table, seq_lens, qo_indptr, accept_len, free_list, free_
         _ptr(page_table, torch.int32), page_table.shape[1], _ptr(seq_lens, torch.int32), _ptr(qo_indptr, torch.int32),
         _ptr(accept_len, torch.int32), _ptr(free_list, torch.int32), free_list.shape[0], _ptr(free_count, torch.int32),
         B, int(page_size), _ptr(status_flags, torch.int32), _stream()))
+
+
+def spec_divergence(p_tokens, p_indptr, h_tokens, h_indptr, delta):
+    B = p_indptr.shape[0] - 1
+    _check(_lib.spec_divergence(_ptr(p_tokens, torch.int32), _ptr(p_indptr, torch.int32), _ptr(h_tokens, torch.int32),
+                                _ptr(h_indptr, torch.int32), _ptr(delta, torch.int32), B, _stream()))
+
+
+def spec_kv_truncate(page_table, seq_lens, keep_len, free_list, free_count, page_size, status_flags):
+    B = seq_lens.shape[0]
+    _check(_lib.spec_kv_truncate(
+        _ptr(page_table, torch.int32), page_table.shape[1], _ptr(seq_lens, torch.int32), _ptr(keep_len, torch.int32),
+        _ptr(free_list, torch.int32), free_list.shape[0], _ptr(free_count, torch.int32), B, int(page_size),
+        _ptr(status_flags, torch.int32), _stream()))
+
+
+def spec_compress_prompts(tokens, indptr, p_num, p_den, out_tokens, out_indptr, kept_index):
+    B = indptr.shape[0] - 1
+    assert out_tokens.numel() >= tokens.numel() and out_indptr.numel() == B + 1
+    _check(_lib.spec_compress_prompts(_ptr(tokens, torch.int32), _ptr(indptr, torch.int32), B, int(p_num), int(p_den),
+                                      _ptr(out_tokens, torch.int32), _ptr(out_indptr, torch.int32),
+                                      _ptr(kept_index, torch.int32), _stream()))
+

@@ -475,6 +475,75 @@ def test_next_round_host_rejections(sv):
     assert int(nqo.cpu()) == 0
 
 
+# --------------------------------------------------------------------------- draft-side primitives
+def _ragged(rows):
+    ip = np.zeros(len(rows) + 1, np.int32)
+    ip[1:] = np.cumsum([len(r) for r in rows])
+    flat = np.array([t for r in rows for t in r] or [0], np.int32)
+    return flat, ip
+
+
+def test_divergence_point_is_bit_exact(sv, oracle):
+    rng = np.random.default_rng(8)
+    p_rows, h_rows = [], []
+    for _ in range(500):
+        n = int(rng.integers(0, 3000)) if rng.random() < 0.9 else 0
+        base = rng.integers(0, 4, n).tolist()
+        other = list(base)
+        if n and rng.random() < 0.7:
+            other[int(rng.integers(0, n))] += 1
+        if n and rng.random() < 0.1:
+            other[0] += 1                                                     # differ at the very first token
+        cut = int(rng.integers(0, n + 1))
+        p_rows.append(base)
+        h_rows.append(other[:cut] if rng.random() < 0.3 else other + [7] * int(rng.integers(0, 3)))
+    pt, pi = _ragged(p_rows)
+    ht, hi = _ragged(h_rows)
+    delta = torch.full((len(p_rows),), -9, dtype=torch.int32, device="cuda")
+    sv.spec_divergence(torch.from_numpy(pt).cuda(), torch.from_numpy(pi).cuda(), torch.from_numpy(ht).cuda(),
+                       torch.from_numpy(hi).cuda(), delta)
+    torch.cuda.synchronize()
+    assert np.array_equal(delta.cpu().numpy(), oracle.divergence(pt, pi, ht, hi))
+
+
+def test_kv_rollback_is_bit_exact(sv, oracle):
+    rng = np.random.default_rng(9)
+    for B in (1, 5, 257, 1500):
+        cfg = wl.VerifyConfig("t", B, B, (0, 2, 4, 8), ("uniform", 0, 300), 8, 1, 64, 64)
+        b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+        lens = (b["seq_lens"].cpu().numpy() + b["gammas"].numpy() + 1).astype(np.int32)   # candidates written: full lengths
+        keep = np.array([rng.integers(-2, l + 5) for l in lens], np.int32)
+        pt, sl = b["page_table"].cpu().numpy().copy(), lens.copy()
+        fl, fc = b["free_list"].cpu().numpy().copy(), b["free_count"].cpu().numpy().copy()
+        oracle.kv_truncate(pt, sl, keep, fl, fc, 16)
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        sl_d = torch.from_numpy(lens).cuda()
+        sv.spec_kv_truncate(b["page_table"], sl_d, torch.from_numpy(keep).cuda(), b["free_list"], b["free_count"], 16, status)
+        torch.cuda.synchronize()
+        assert np.array_equal(b["page_table"].cpu().numpy(), pt) and np.array_equal(sl_d.cpu().numpy(), sl)
+        assert int(b["free_count"].cpu()) == int(fc[0])
+        assert np.array_equal(b["free_list"].cpu().numpy()[:int(fc[0])], fl[:int(fc[0])])
+        assert int(status.cpu()) == 0
+
+
+@pytest.mark.parametrize("p_num,p_den", [(1, 10), (1, 4), (2, 3), (0, 1), (7, 5)])
+def test_prompt_compression_is_bit_exact(sv, oracle, p_num, p_den):
+    rng = np.random.default_rng(p_num * 10 + p_den)
+    rows = [rng.integers(0, 50000, int(rng.integers(0, 9000))).tolist() for _ in range(90)]
+    rows[3] = []
+    flat, ip = _ragged(rows)
+    out = torch.full((len(flat) + 8,), -9, dtype=torch.int32, device="cuda")
+    idx = torch.full((len(flat) + 8,), -9, dtype=torch.int32, device="cuda")
+    oip = torch.full((len(rows) + 1,), -9, dtype=torch.int32, device="cuda")
+    sv.spec_compress_prompts(torch.from_numpy(flat).cuda(), torch.from_numpy(ip).cuda(), p_num, p_den, out, oip, idx)
+    torch.cuda.synchronize()
+    want, woip, widx = oracle.compress_prompts(flat, ip, p_num, p_den)
+    n = len(want)
+    assert np.array_equal(oip.cpu().numpy(), woip)
+    assert np.array_equal(out.cpu().numpy()[:n], want) and (out.cpu().numpy()[n:] == -9).all()
+    assert np.array_equal(idx.cpu().numpy()[:n], widx)
+
+
 # --------------------------------------------------------------------------- whole step
 def _run_step(sv, oracle, cfg, stochastic, fused=False):
     b = wl.make_batch(cfg, device="cuda")
