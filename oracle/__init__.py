@@ -212,3 +212,45 @@ def compress_prompts(tokens, indptr, p_num, p_den):
     _check(min(n, 0), "oracle_compress_prompts")
     return out[:n].copy(), oip, idx[:n].copy()
 
+
+def verify_attn_tree(q, k_cache, v_cache, page_table, seq_lens, qo_indptr, parent, scale, want_lse=False):
+    """Tree attention: row j sees the committed prefix and its own root path (Appendix, "Unified verification interface")."""
+    M, Hq, D = q.shape
+    _, Hkv, P, _ = k_cache.shape
+    B = seq_lens.shape[0]
+    out = np.zeros((M, Hq, D), np.float32)
+    lse = np.zeros((M, Hq), np.float32) if want_lse else None
+    rc = _load().oracle_verify_attn_tree(
+        _p(q, np.uint16), _p(k_cache, np.uint16), _p(v_cache, np.uint16), _p(page_table, np.int32),
+        ctypes.c_int(page_table.shape[1]), _p(seq_lens, np.int32), _p(qo_indptr, np.int32), _p(parent, np.int32),
+        _p(out, np.float32), _p(lse, np.float32), B, M, Hq, Hkv, D, P, ctypes.c_float(scale))
+    _check(rc, "oracle_verify_attn_tree")
+    return (out, lse) if want_lse else out
+
+
+def accept_tree(logits, tokens, parent, qo_indptr, gamma_max):
+    M, V = logits.shape
+    B = qo_indptr.shape[0] - 1
+    accept_len = np.zeros(B, np.int32)
+    out_tokens = np.zeros((B, gamma_max + 1), np.int32)
+    path = np.zeros((B, gamma_max + 1), np.int32)
+    rollback = np.zeros(B, np.uint8)
+    status = np.zeros(1, np.int32)
+    rc = _load().oracle_accept_tree(_p(logits, np.float32), _p(tokens, np.int32), _p(parent, np.int32), _p(qo_indptr, np.int32),
+                                    _p(accept_len, np.int32), _p(out_tokens, np.int32), _p(path, np.int32),
+                                    _p(rollback, np.uint8), _p(status, np.int32), B, M, V, gamma_max)
+    _check(rc, "oracle_accept_tree")
+    return dict(accept_len=accept_len, out_tokens=out_tokens, path=path, rollback=rollback, status=int(status[0]))
+
+
+def kv_commit_tree(k_cache, v_cache, page_table, seq_lens, qo_indptr, accept_len, path, free_list, free_count, page_size):
+    """In place: gathers the accepted path's K/V to positions c+1.., then commits as kv_commit."""
+    B = seq_lens.shape[0]
+    _, Hkv, P, D = k_cache.shape
+    rc = _load().oracle_kv_commit_tree(
+        _p(k_cache, np.uint16), _p(v_cache, np.uint16), _p(page_table, np.int32), ctypes.c_int(page_table.shape[1]),
+        _p(seq_lens, np.int32), _p(qo_indptr, np.int32), _p(accept_len, np.int32), _p(path, np.int32),
+        ctypes.c_int(path.shape[1] - 1), _p(free_list, np.int32), ctypes.c_int32(free_list.shape[0]),
+        _p(free_count, np.int32), B, Hkv, D, page_size)
+    _check(rc, "oracle_kv_commit_tree")
+

@@ -531,3 +531,168 @@ long oracle_compress_prompts(const int32_t* tokens, const int32_t* indptr, int B
     return n;
 }
 
+/* ------------------------------------------------------------------------- *
+ * Tree-structured verification (Appendix "Target side", "Unified verification
+ * interface": the remote tokens are turned into a verification tree T_n^(i);
+ * a single remote sequence is the chain handled above).  The candidate rows of
+ * a request form a tree: row 0 is the root (the last committed / bonus token),
+ * parent[r0 + j] is the row-local index of the parent of row j (parent < j,
+ * -1 for the root).  The K/V of row j sits at cache position c_i + j.
+ *
+ * Attention: row j attends to the committed prefix 0 .. c_i - 1 and to the
+ * candidate rows on its own path to the root, itself included.
+ * ------------------------------------------------------------------------- */
+static int tree_ok(const int32_t* parent, int n)
+{
+    if (n < 1 || parent[0] != -1) return 0;
+    for (int j = 1; j < n; ++j) if (parent[j] < 0 || parent[j] >= j) return 0;
+    return 1;
+}
+
+int oracle_verify_attn_tree(const uint16_t* q, const uint16_t* k_cache, const uint16_t* v_cache,
+                            const int32_t* page_table, int max_pages_per_seq,
+                            const int32_t* seq_lens, const int32_t* qo_indptr, const int32_t* parent,
+                            float* out, float* lse,
+                            int B, int M, int Hq, int Hkv, int D, int page_size, float scale)
+{
+    if (!q || !k_cache || !v_cache || !page_table || !seq_lens || !qo_indptr || !parent || !out) return ORACLE_EINVAL;
+    if (B < 0 || M < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || page_size <= 0 || Hq % Hkv) return ORACLE_EINVAL;
+    const int G = Hq / Hkv;
+    int status = ORACLE_OK;
+    for (int i = 0; i < B; ++i) {
+        const int r0 = qo_indptr[i], n = qo_indptr[i + 1] - qo_indptr[i], c = seq_lens[i];
+        if (!tree_ok(parent + r0, n)) { status = ORACLE_EINVAL; continue; }
+        char* visible = (char*)malloc((size_t)(c + n));
+        double* s = (double*)malloc(sizeof(double) * (size_t)(c + n));
+        double* acc = (double*)malloc(sizeof(double) * (size_t)D);
+        for (int j = 0; j < n; ++j) {
+            for (int t = 0; t < c + n; ++t) visible[t] = t < c;
+            for (int a = j; a >= 0; a = parent[r0 + a]) visible[c + a] = 1;
+            for (int h = 0; h < Hq; ++h) {
+                const int kvh = h / G, row = r0 + j;
+                const uint16_t* qv = q + ((size_t)row * Hq + h) * D;
+                double m = -INFINITY;
+                for (int t = 0; t < c + n; ++t) {
+                    if (!visible[t]) continue;
+                    const int page = page_table[(size_t)i * max_pages_per_seq + t / page_size];
+                    if (page < 0) { status = ORACLE_EINVAL; visible[t] = 0; continue; }
+                    const uint16_t* kv = k_cache + (((size_t)page * Hkv + kvh) * page_size + t % page_size) * D;
+                    double dot = 0.0;
+                    for (int d = 0; d < D; ++d) dot += (double)bf16_bits_to_float(qv[d]) * (double)bf16_bits_to_float(kv[d]);
+                    s[t] = (double)scale * dot;
+                    if (s[t] > m) m = s[t];
+                }
+                for (int d = 0; d < D; ++d) acc[d] = 0.0;
+                double denom = 0.0;
+                for (int t = 0; t < c + n; ++t) {
+                    if (!visible[t]) continue;
+                    const int page = page_table[(size_t)i * max_pages_per_seq + t / page_size];
+                    const double w = exp(s[t] - m);
+                    denom += w;
+                    const uint16_t* vv = v_cache + (((size_t)page * Hkv + kvh) * page_size + t % page_size) * D;
+                    for (int d = 0; d < D; ++d) acc[d] += w * (double)bf16_bits_to_float(vv[d]);
+                }
+                float* o = out + ((size_t)row * Hq + h) * D;
+                for (int d = 0; d < D; ++d) o[d] = (float)(acc[d] / denom);
+                if (lse) lse[(size_t)row * Hq + h] = (float)(m + log(denom));
+            }
+        }
+        free(visible); free(s); free(acc);
+    }
+    return status;
+}
+
+/* Greedy acceptance on a tree: from the root, follow the child whose token is the argmax of the current
+ * node's logits row (lowest index wins ties; the lowest row among equal children) as long as there is one.
+ * accept_len = drafts accepted, out_tokens = their tokens then the bonus (the argmax at the last node), path =
+ * row-local indices of the visited nodes (path[0] = 0), -1 padded.  rollback = the last node still had children
+ * (the drafter went on from it, but not with the token the target produced).  A NaN row, a row maximum that is
+ * not finite, a token outside [0, V) or a malformed tree: a = 0, tokens -1, path = {0}, a status bit. */
+int oracle_accept_tree(const float* logits, const int32_t* tokens, const int32_t* parent, const int32_t* qo_indptr,
+                       int32_t* accept_len, int32_t* out_tokens, int32_t* path, uint8_t* rollback, int32_t* status_flags,
+                       int B, int M, int V, int gamma_max)
+{
+    if (!logits || !tokens || !parent || !qo_indptr || !accept_len || !out_tokens || !path) return ORACLE_EINVAL;
+    if (B < 0 || M < 0 || V <= 0 || gamma_max < 0) return ORACLE_EINVAL;
+    for (int i = 0; i < B; ++i) {
+        const int r0 = qo_indptr[i], n = qo_indptr[i + 1] - qo_indptr[i];
+        int32_t* emit = out_tokens + (size_t)i * (gamma_max + 1);
+        int32_t* pth = path + (size_t)i * (gamma_max + 1);
+        for (int k = 0; k <= gamma_max; ++k) { emit[k] = -1; pth[k] = -1; }
+        pth[0] = 0;
+        accept_len[i] = 0;
+        if (rollback) rollback[i] = 0;
+        int flags = 0;
+        if (n < 1 || n - 1 > gamma_max || !tree_ok(parent + r0, n)) flags |= 2;
+        int* arg = (int*)malloc(sizeof(int) * (size_t)(n > 0 ? n : 1));
+        if (!flags) {
+            for (int j = 0; j < n; ++j) {
+                const float* l = logits + (size_t)(r0 + j) * V;
+                int best = 0, bad = 0;
+                for (int v = 0; v < V; ++v) { if (l[v] != l[v]) bad = 1; if (l[v] > l[best]) best = v; }
+                if (bad || !(l[best] > -INFINITY && l[best] < INFINITY)) flags |= 4;
+                arg[j] = best;
+                if (j > 0 && (tokens[r0 + j] < 0 || tokens[r0 + j] >= V)) flags |= 8;
+            }
+        }
+        if (flags) {
+            if (status_flags) *status_flags |= flags;
+            if (rollback) rollback[i] = (uint8_t)(n > 1);
+            free(arg);
+            continue;
+        }
+        int u = 0, a = 0;
+        for (;;) {
+            int next = -1;
+            for (int v = u + 1; v < n; ++v)
+                if (parent[r0 + v] == u && tokens[r0 + v] == arg[u]) { next = v; break; }
+            if (next < 0) break;
+            emit[a] = tokens[r0 + next];
+            ++a;
+            pth[a] = next;
+            u = next;
+        }
+        emit[a] = arg[u];
+        accept_len[i] = a;
+        int has_child = 0;
+        for (int v = u + 1; v < n; ++v) if (parent[r0 + v] == u) has_child = 1;
+        if (rollback) rollback[i] = (uint8_t)has_child;
+        free(arg);
+    }
+    return ORACLE_OK;
+}
+
+/* Commit of an accepted tree path: the K/V of the accepted nodes (cache positions c + path[k], k = 1 .. a) are
+ * moved to positions c + 1 .. c + a, so that the committed prefix is contiguous again; then lengths, page table
+ * and free list are updated exactly as by oracle_kv_commit (new length c + a + 1). */
+int oracle_kv_commit_tree(uint16_t* k_cache, uint16_t* v_cache, int32_t* page_table, int max_pages_per_seq,
+                          int32_t* seq_lens, const int32_t* qo_indptr, const int32_t* accept_len,
+                          const int32_t* path, int gamma_max,
+                          int32_t* free_list, int32_t free_capacity, int32_t* free_count,
+                          int B, int Hkv, int D, int page_size)
+{
+    if (!k_cache || !v_cache || !page_table || !seq_lens || !qo_indptr || !accept_len || !path) return ORACLE_EINVAL;
+    for (int i = 0; i < B; ++i) {
+        const int n = qo_indptr[i + 1] - qo_indptr[i], c = seq_lens[i];
+        int a = accept_len[i];
+        if (a < 0) a = 0;
+        if (a > n - 1) a = n - 1;
+        for (int k = 1; k <= a; ++k) {
+            const int src = c + path[(size_t)i * (gamma_max + 1) + k], dst = c + k;
+            if (src == dst) continue;
+            if (src < dst || src >= c + n) return ORACLE_EINVAL;
+            const int ps = page_table[(size_t)i * max_pages_per_seq + src / page_size];
+            const int pd = page_table[(size_t)i * max_pages_per_seq + dst / page_size];
+            if (ps < 0 || pd < 0) return ORACLE_EINVAL;
+            for (int h = 0; h < Hkv; ++h) {
+                const size_t so = (((size_t)ps * Hkv + h) * page_size + src % page_size) * D;
+                const size_t dn = (((size_t)pd * Hkv + h) * page_size + dst % page_size) * D;
+                memcpy(k_cache + dn, k_cache + so, sizeof(uint16_t) * (size_t)D);
+                memcpy(v_cache + dn, v_cache + so, sizeof(uint16_t) * (size_t)D);
+            }
+        }
+    }
+    return oracle_kv_commit(page_table, max_pages_per_seq, seq_lens, qo_indptr, accept_len, free_list, free_capacity,
+                            free_count, B, page_size);
+}
+
