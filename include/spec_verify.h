@@ -57,6 +57,7 @@ extern "C" {
 #define SPEC_FLAG_BAD_TOKEN 8     /* draft token id outside [0, V) */
 #define SPEC_FLAG_FREE_OVERFLOW 16 /* free list capacity exceeded in spec_kv_commit */
 #define SPEC_FLAG_NO_SEED 32      /* temperature > 0 but seeds == NULL */
+#define SPEC_FLAG_BAD_TREE 64     /* parent[] of a request is not a tree in topological order */
 
 /* Text of the calling thread's last error ("" if none). host. */
 const char* spec_last_error_string(void);
@@ -108,6 +109,22 @@ int spec_verify_attn(const void* q, const void* k_cache, const void* v_cache,
                      int max_kv_len, int max_q_len, float scale,
                      int32_t* status_flags,
                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* spec_verify_attn for tree-structured candidates (Appendix "Target side", "Unified verification interface": the
+ * remote tokens become a verification tree; one remote sequence is the chain that spec_verify_attn handles).
+ * parent [M] int32 (device): for every candidate row the row-local index of its parent inside its request,
+ * -1 for the root (row 0), parent < own index; NULL = chains, identical to spec_verify_attn.  Row j attends to the
+ * committed prefix and to the candidate rows on its own path to the root, itself included; the K/V of row j sits at
+ * cache position c_i + j as before.  At most 64 rows per request (SPEC_ESHAPE beyond); a request whose parent[]
+ * is not such a tree is skipped and SPEC_FLAG_BAD_TREE is raised.  Everything else as spec_verify_attn. */
+int spec_verify_attn_tree(const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* page_table, int max_pages_per_seq, int num_pages,
+                          const int32_t* seq_lens, const int32_t* qo_indptr, const int32_t* parent,
+                          void* out, float* lse,
+                          int B, int M, int Hq, int Hkv, int D, int page_size,
+                          int max_kv_len, int max_q_len, float scale,
+                          int32_t* status_flags,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
  * spec_lm_head — logits of every candidate position (each position of Y_n is
@@ -301,6 +318,41 @@ int spec_kv_truncate(int32_t* page_table, int max_pages_per_seq, int32_t* seq_le
 
 int spec_compress_prompts(const int32_t* tokens, const int32_t* indptr, int B, int p_num, int p_den,
                           int32_t* out_tokens, int32_t* out_indptr, int32_t* kept_index, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Tree-structured verification, acceptance and commit (Appendix "Target side",
+ * "Unified verification interface").  Attention: spec_verify_attn_tree above.
+ *
+ * spec_accept_tree — greedy (temperature 0) acceptance on candidate trees: from
+ *   the root, at node u the target's token is the argmax of logits row u (lowest
+ *   index on ties); the walk moves to the child of u that carries this token
+ *   (the lowest row among equal children) and ends where there is none.
+ *   tokens [M], parent [M] (as for spec_verify_attn_tree), logits [M, V] fp32.
+ *   Outputs: accept_len [B] = drafts accepted, out_tokens [B, gamma_max+1] =
+ *   their tokens, the bonus (argmax at the last node), then -1; path
+ *   [B, gamma_max+1] = row-local indices of the visited nodes (path[0] = 0),
+ *   then -1; rollback [B] or NULL = the last node still had children; stats [4]
+ *   or NULL as for spec_accept.  Bad rows / tokens / trees: a = 0, tokens -1,
+ *   path {0}, and SPEC_FLAG_BAD_LOGITS / _BAD_TOKEN / _BAD_TREE.  Workspace:
+ *   spec_accept_workspace_bytes.  Sampling on trees is not built.
+ *
+ * spec_kv_commit_tree — the K/V of the accepted nodes (cache positions
+ *   c_i + path[k]) are moved to c_i + k, k = 1 .. a_i, then lengths, page table
+ *   and free list are updated exactly as by spec_kv_commit.  k_cache / v_cache
+ *   [num_pages, Hkv, page_size, D] bf16 are modified in place.  A path that is
+ *   not increasing with path[k] >= k raises SPEC_FLAG_BAD_TREE and moves nothing
+ *   further for that request.
+ * ------------------------------------------------------------------------- */
+int spec_accept_tree(const float* logits, const int32_t* tokens, const int32_t* parent,
+                     const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens, int32_t* path,
+                     uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                     int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream);
+
+int spec_kv_commit_tree(void* k_cache, void* v_cache, int32_t* page_table, int max_pages_per_seq, int num_pages,
+                        int32_t* seq_lens, const int32_t* qo_indptr, const int32_t* accept_len,
+                        const int32_t* path, int gamma_max,
+                        int32_t* free_list, int32_t free_capacity, int32_t* free_count,
+                        int B, int Hkv, int D, int page_size, int32_t* status_flags, void* stream);
 
 #ifdef __cplusplus
 }

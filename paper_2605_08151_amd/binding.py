@@ -20,9 +20,11 @@ EXPORTS = (
     "spec_accept_workspace_bytes", "spec_accept", "spec_kv_commit", "spec_next_mode",
     "spec_lm_head_stats_blocks", "spec_lm_head_stats", "spec_accept_stats", "spec_assemble_next",
     "spec_divergence", "spec_kv_truncate", "spec_compress_prompts",
+    "spec_verify_attn_tree", "spec_accept_tree", "spec_kv_commit_tree",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
+FLAG_BAD_TREE = 64
 
 
 class SpecError(RuntimeError):
@@ -60,6 +62,13 @@ def _load():
     lib.spec_lm_head_stats.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
     lib.spec_accept_stats.restype = i32
     lib.spec_accept_stats.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
+    lib.spec_verify_attn_tree.restype = i32
+    lib.spec_verify_attn_tree.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp,
+                                          i32, i32, i32, i32, i32, i32, i32, i32, f32, vp, vp, sz, vp]
+    lib.spec_accept_tree.restype = i32
+    lib.spec_accept_tree.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.spec_kv_commit_tree.restype = i32
+    lib.spec_kv_commit_tree.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp, i32, i32, i32, i32, vp, vp]
     lib.spec_divergence.restype = i32
     lib.spec_divergence.argtypes = [vp, vp, vp, vp, vp, i32, vp]
     lib.spec_kv_truncate.restype = i32
@@ -226,4 +235,40 @@ def spec_compress_prompts(tokens, indptr, p_num, p_den, out_tokens, out_indptr, 
     _check(_lib.spec_compress_prompts(_ptr(tokens, torch.int32), _ptr(indptr, torch.int32), B, int(p_num), int(p_den),
                                       _ptr(out_tokens, torch.int32), _ptr(out_indptr, torch.int32),
                                       _ptr(kept_index, torch.int32), _stream()))
+
+
+def spec_verify_attn_tree(q, k_cache, v_cache, page_table, seq_lens, qo_indptr, parent, out, lse, max_kv_len, max_q_len, scale,
+                          status_flags, workspace):
+    M, Hq, D = q.shape
+    num_pages, Hkv, P, _ = k_cache.shape
+    B = seq_lens.shape[0]
+    _check(_lib.spec_verify_attn_tree(
+        _ptr(q, torch.bfloat16), _ptr(k_cache, torch.bfloat16), _ptr(v_cache, torch.bfloat16),
+        _ptr(page_table, torch.int32), page_table.shape[1], num_pages, _ptr(seq_lens, torch.int32),
+        _ptr(qo_indptr, torch.int32), _ptr(parent, torch.int32), _ptr(out, torch.bfloat16), _ptr(lse, torch.float32),
+        B, M, Hq, Hkv, D, P, int(max_kv_len), int(max_q_len), float(scale), _ptr(status_flags, torch.int32),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def spec_accept_tree(logits, tokens, parent, qo_indptr, accept_len, out_tokens, path, rollback, stats, gamma_max,
+                     status_flags, workspace):
+    M, V = logits.shape
+    B = qo_indptr.shape[0] - 1
+    assert tuple(out_tokens.shape) == (B, gamma_max + 1) and tuple(path.shape) == (B, gamma_max + 1)
+    _check(_lib.spec_accept_tree(
+        _ptr(logits, torch.float32), _ptr(tokens, torch.int32), _ptr(parent, torch.int32), _ptr(qo_indptr, torch.int32),
+        _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), _ptr(path, torch.int32), _ptr(rollback, torch.uint8),
+        _ptr(stats, torch.int32), B, M, V, int(gamma_max), _ptr(status_flags, torch.int32),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def spec_kv_commit_tree(k_cache, v_cache, page_table, seq_lens, qo_indptr, accept_len, path, free_list, free_count,
+                        status_flags):
+    num_pages, Hkv, P, D = k_cache.shape
+    B = seq_lens.shape[0]
+    _check(_lib.spec_kv_commit_tree(
+        _ptr(k_cache, torch.bfloat16), _ptr(v_cache, torch.bfloat16), _ptr(page_table, torch.int32), page_table.shape[1],
+        num_pages, _ptr(seq_lens, torch.int32), _ptr(qo_indptr, torch.int32), _ptr(accept_len, torch.int32),
+        _ptr(path, torch.int32), path.shape[1] - 1, _ptr(free_list, torch.int32), free_list.shape[0],
+        _ptr(free_count, torch.int32), B, Hkv, D, P, _ptr(status_flags, torch.int32), _stream()))
 

@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
         const int v0 = (seg0 + q) * kSeg;
         load_strided(lrow, min(v0, V), min(V, v0 + kSeg), vec, tid, x[q]);      // past the row: all -inf
     }
-    const float T = temperature[find_request(qo_indptr, B, row)];
+    const float T = temperature ? temperature[find_request(qo_indptr, B, row)] : 0.0f;   // null: every request greedy
     if (greedy_rows_covered && T == 0.0f) return;         // the decision reads the LM head's block statistics instead
 #pragma unroll
     for (int q = 0; q < kSegPerWg; ++q) {
@@ -390,6 +390,78 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
     if (rollback) rollback[i] = (uint8_t)(a < gamma);
     if (stats) {
         if (a < gamma) atomicAdd(stats + 0, 1);
+        atomicAdd(stats + 1, a + 1);
+    }
+}
+
+// ---- 2b. greedy decision on a candidate tree ---------------------------------------------------
+// Same merge of the per-segment maxima as above; then one thread walks from the root: at node u the target's
+// token is the argmax of row u; the walk goes on to the child of u that carries it (the lowest row among equal
+// children) and stops where there is none.  path = the visited rows, out_tokens = their tokens then the bonus.
+__global__ __launch_bounds__(256) void accept_decide_tree_kernel(
+    const int32_t* __restrict__ tokens, const int32_t* __restrict__ parent, const int32_t* __restrict__ qo_indptr,
+    int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens, int32_t* __restrict__ path,
+    uint8_t* __restrict__ rollback, int32_t* __restrict__ stats, int M, int V, int nseg, int gamma_max,
+    AcceptWorkspace w, int32_t* __restrict__ status_flags)
+{
+    __shared__ int s_arg[kMaxRows], s_bad[kMaxRows], s_tok[kMaxRows], s_par[kMaxRows];
+    const int i = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tid = threadIdx.x;
+    const int r0 = qo_indptr[i], n = qo_indptr[i + 1] - r0;
+    int32_t* emit = out_tokens + (size_t)i * (gamma_max + 1);
+    int32_t* pth = path + (size_t)i * (gamma_max + 1);
+    for (int j = tid; j <= gamma_max; j += 256) { emit[j] = -1; pth[j] = j == 0 ? 0 : -1; }
+    if (tid == 0) { accept_len[i] = 0; if (rollback) rollback[i] = 0; }
+    if (n < 1 || n - 1 > gamma_max || r0 < 0 || r0 + n > M) {
+        if (tid == 0 && status_flags) atomicOr(status_flags, SPEC_FLAG_BAD_LENGTH);
+        return;
+    }
+    for (int j = wave; j < n; j += 4) {
+        const size_t base = (size_t)(r0 + j) * nseg;
+        float m = -INFINITY;
+        int arg = 0x7FFFFFFF, bad = 0;
+        for (int s = lane; s < nseg; s += 64) {
+            const float sm = w.seg_max[base + s];
+            const int sa = w.seg_arg[base + s];
+            bad |= w.seg_bad[base + s];
+            if (sm > m || (sm == m && sa < arg)) { m = sm; arg = sa; }
+        }
+        wave_max_arg(m, arg);
+        bad = __any(bad) || !(m > -INFINITY && m < INFINITY);
+        if (lane == 0) { s_arg[j] = arg; s_bad[j] = bad; }
+    }
+    if (tid < n) { s_tok[tid] = tokens[r0 + tid]; s_par[tid] = parent[r0 + tid]; }
+    __syncthreads();
+    if (tid != 0) return;
+    int flags = 0;
+    for (int j = 0; j < n; ++j) {
+        if (s_bad[j]) flags |= SPEC_FLAG_BAD_LOGITS;
+        if (j > 0 && (s_tok[j] < 0 || s_tok[j] >= V)) flags |= SPEC_FLAG_BAD_TOKEN;
+        if (j == 0 ? s_par[0] != -1 : (s_par[j] < 0 || s_par[j] >= j)) flags |= SPEC_FLAG_BAD_TREE;
+    }
+    if (flags) {
+        if (rollback) rollback[i] = (uint8_t)(n > 1);
+        if (stats && n > 1) atomicAdd(stats + 0, 1);
+        if (status_flags) atomicOr(status_flags, flags);
+        return;
+    }
+    int u = 0, a = 0;
+    for (;;) {
+        int next = -1;
+        for (int v = u + 1; v < n; ++v)
+            if (s_par[v] == u && s_tok[v] == s_arg[u]) { next = v; break; }
+        if (next < 0) break;
+        emit[a] = s_tok[next];
+        ++a;
+        pth[a] = next;
+        u = next;
+    }
+    emit[a] = s_arg[u];
+    accept_len[i] = a;
+    int has_child = 0;
+    for (int v = u + 1; v < n; ++v) has_child |= (s_par[v] == u);
+    if (rollback) rollback[i] = (uint8_t)has_child;
+    if (stats) {
+        if (has_child) atomicAdd(stats + 0, 1);
         atomicAdd(stats + 1, a + 1);
     }
 }
@@ -618,3 +690,37 @@ extern "C" int spec_accept(const float* logits, const int32_t* tokens, const flo
                              rollback, stats, B, M, V, gamma_max, nullptr, nullptr, 0, status_flags, workspace,
                              workspace_bytes, stream);
 }
+
+extern "C" int spec_accept_tree(const float* logits, const int32_t* tokens, const int32_t* parent,
+                                const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens, int32_t* path,
+                                uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                                int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace specv;
+    if (B < 0 || M < 0 || V <= 0 || gamma_max < 0)
+        return fail(SPEC_EINVAL, "spec_accept_tree: negative size (B=%d M=%d V=%d gamma_max=%d)", B, M, V, gamma_max);
+    if (B == 0) return SPEC_OK;
+    if (!logits || !tokens || !parent || !qo_indptr || !accept_len || !out_tokens || !path)
+        return fail(SPEC_EINVAL, "spec_accept_tree: NULL pointer argument");
+    if (gamma_max + 1 > kMaxRows)
+        return fail(SPEC_ESHAPE, "spec_accept_tree: gamma_max=%d, at most %d candidate rows per request", gamma_max, kMaxRows);
+    if (M < B) return fail(SPEC_EINVAL, "spec_accept_tree: M=%d < B=%d (every request has at least one row)", M, B);
+    const int nseg = accept_nseg(V);
+    if (nseg > 65535 || M > 65535 || B > 65535)
+        return fail(SPEC_ESHAPE, "spec_accept_tree: V=%d or M=%d beyond the launch grid", V, M);
+    AcceptWorkspace w;
+    const size_t need = carve(&w, nullptr, B, M, nseg);
+    if (!workspace || !aligned(workspace, 256))
+        return fail(SPEC_EINVAL, "spec_accept_tree: workspace is NULL or not 256-byte aligned");
+    if (workspace_bytes < need)
+        return fail(SPEC_EWORKSPACE, "spec_accept_tree: workspace %zu bytes, need %zu", workspace_bytes, need);
+    carve(&w, (char*)workspace, B, M, nseg);
+    const bool vec = (V % 4 == 0) && aligned(logits, 16);
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(accept_row_stats_kernel, dim3((nseg + kSegPerWg - 1) / kSegPerWg, M), dim3(kThreads), 0, s, logits,
+                       (const float*)nullptr, qo_indptr, B, V, nseg, vec, w, stats, false);
+    hipLaunchKernelGGL(accept_decide_tree_kernel, dim3(B), dim3(256), 0, s, tokens, parent, qo_indptr, accept_len, out_tokens,
+                       path, rollback, stats, M, V, nseg, gamma_max, w, status_flags);
+    return check_launch("spec_accept_tree");
+}
+

@@ -57,6 +57,7 @@ struct AttnParams {
     // balanced work list written by verify_attn_plan_kernel (all null when requests are split by the fixed
     // chunk_target instead): hdr = {items, keys per chunk}; req[i] = {splits of request i, first partial slot};
     // items[k] = {request, split, splits of the request, first partial slot}
+    const int32_t* parent;     // tree verification: row-local parent of every candidate row ([M], -1 for a root), or null = chains
     const int32_t* plan_hdr;
     const int32_t* plan_req;
     const int32_t* plan_items;
@@ -169,6 +170,38 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
         const int r = rt * 16 + l16;
         limit[rt] = (r < R) ? min(c + r / G + 1, kend) : 0;
     }
+    // Tree verification: candidate row j sees the committed prefix and the rows on its own path to the root.
+    // anc[rt] has bit a set iff candidate a is such a row for this lane's query row (n <= 64 in this mode).
+    const bool tree = p.parent != nullptr;
+    // (the masks live in LDS and are read in the few steps that reach the candidates: in registers they would
+    // cost every step of the loop two registers per row tile)
+    int32_t* sPar = sPT + (min(p.chunk_target, p.max_kv_len) / kP + 1);
+    unsigned long long* sAnc = reinterpret_cast<unsigned long long*>(sPar + 64);   // [NR * 16], 8-byte aligned
+    if (tree) {
+        int bad_tree = 0;
+        if (tid < n) {
+            const int par = p.parent[r0 + tid];
+            sPar[tid] = par;
+            bad_tree = tid == 0 ? par != -1 : (par < 0 || par >= tid);
+        }
+        if (__syncthreads_or(bad_tree)) {                 // uniform: the whole workgroup leaves the request alone
+            if (tid == 0 && split == 0 && kvh == 0 && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_TREE);
+            __builtin_amdgcn_s_waitcnt(0x0F70);           // the first step's direct loads have landed before the LDS is given up
+            return;
+        }
+#pragma unroll
+        for (int rt = 0; rt < NR; ++rt) limit[rt] = (rt * 16 + l16 < R) ? kend : 0;
+    }
+    // chains: every candidate below the causal limit is on the path (all bits set), so one masking loop serves both
+    for (int r = tid; r < NR * 16; r += kThreads) {
+        unsigned long long m = ~0ull;
+        if (tree) {
+            m = 0ull;
+            if (r < R)
+                for (int a = r / G; a >= 0; a = sPar[a]) m |= 1ull << a;
+        }
+        sAnc[r] = m;
+    }
     __syncthreads();
 
     f32x4 o[NR][8];
@@ -241,12 +274,18 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
         }
         if (need_mask) {
 #pragma unroll
-            for (int rt = 0; rt < A; ++rt)
+            for (int rt = 0; rt < A; ++rt) {
+                const unsigned long long anc = sAnc[rt * 16 + l16];
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if ((wbase + kb * 16 + g * 4 + e) >= limit[rt]) sc[rt][kb * 4 + e] = kNegBig;   // exp2 of it is 0
+                    for (int e = 0; e < 4; ++e) {
+                        const int t = wbase + kb * 16 + g * 4 + e, rel = t - c;
+                        // a tree has at most 64 candidates (rel < 64 below the limit); a chain's mask is all ones
+                        const bool seen = t < limit[rt] && (rel < 0 || ((anc >> (rel & 63)) & 1ull));
+                        if (!seen) sc[rt][kb * 4 + e] = kNegBig;                       // exp2 of it is 0
+                    }
+            }
         }
         float tmax[A];
 #pragma unroll
@@ -659,7 +698,7 @@ static AttnPlanCfg attn_plan_cfg(int B, int Hq, int Hkv, int max_kv_len, int max
 
 static size_t attn_smem_bytes(int NR, int NW, int NBUF, int chunk_keys)
 {
-    const size_t tiles = (size_t)NW * NBUF * kWaveLds + (size_t)NR * 16 * kRowBytes + (size_t)(chunk_keys / kP + 1) * 4;
+    const size_t tiles = (size_t)NW * NBUF * kWaveLds + (size_t)NR * 16 * kRowBytes + (size_t)(chunk_keys / kP + 1) * 4 + 64 * 4 + 8 + (size_t)NR * 16 * 8;
     const size_t epi = (size_t)(2 * NW * NR * 16 + 2 * NR * 16 + NW * NR * 16 * kRedPitch) * sizeof(float);
     return tiles > epi ? tiles : epi;
 }
@@ -715,7 +754,22 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
                                 int max_kv_len, int max_q_len, float scale, int32_t* status_flags,
                                 void* workspace, size_t workspace_bytes, void* stream)
 {
+    return spec_verify_attn_tree(q, k_cache, v_cache, page_table, max_pages_per_seq, num_pages, seq_lens, qo_indptr,
+                                 nullptr, out, lse, B, M, Hq, Hkv, D, page_size, max_kv_len, max_q_len, scale,
+                                 status_flags, workspace, workspace_bytes, stream);
+}
+
+extern "C" int spec_verify_attn_tree(const void* q, const void* k_cache, const void* v_cache,
+                                     const int32_t* page_table, int max_pages_per_seq, int num_pages,
+                                     const int32_t* seq_lens, const int32_t* qo_indptr, const int32_t* parent,
+                                     void* out, float* lse,
+                                     int B, int M, int Hq, int Hkv, int D, int page_size,
+                                     int max_kv_len, int max_q_len, float scale, int32_t* status_flags,
+                                     void* workspace, size_t workspace_bytes, void* stream)
+{
     using namespace specv;
+    if (parent && max_q_len > 64)
+        return fail(SPEC_ESHAPE, "spec_verify_attn_tree: max_q_len=%d, a tree has at most 64 rows", max_q_len);
     if (B == 0 || M == 0) return SPEC_OK;
     if (!q || !k_cache || !v_cache || !page_table || !seq_lens || !qo_indptr || !out)
         return fail(SPEC_EINVAL, "spec_verify_attn: NULL pointer argument");
@@ -750,6 +804,7 @@ extern "C" int spec_verify_attn(const void* q, const void* k_cache, const void* 
     p.splits = (max_kv_len + p.chunk_target - 1) / p.chunk_target;
     p.scale_log2e = scale * 1.4426950408889634f;
     p.plan_hdr = nullptr; p.plan_req = nullptr; p.plan_items = nullptr;
+    p.parent = parent;
     hipStream_t s = (hipStream_t)stream;
     char* ws = (char*)workspace;
     const AttnPlanCfg pc = attn_plan_cfg(B, Hq, Hkv, max_kv_len, max_q_len, NR, p.chunk_target);

@@ -544,6 +544,147 @@ def test_prompt_compression_is_bit_exact(sv, oracle, p_num, p_den):
     assert np.array_equal(idx.cpu().numpy()[:n], widx)
 
 
+# --------------------------------------------------------------------------- tree-structured verification
+def _random_parents(rng, gammas):
+    out = []
+    for g in gammas:
+        out.append(-1)
+        out += [int(rng.integers(0, j)) for j in range(1, int(g) + 1)]
+    return np.array(out, np.int32)
+
+
+TREE_CASES = [
+    # name, B, gammas, ctx, Hq, Hkv
+    ("tree_g8", 5, (0, 2, 4, 8), ("uniform", 1, 700), 8, 1),
+    ("tree_gqa", 6, (4, 7), ("uniform", 100, 1500), 32, 8),
+    ("tree_15", 3, (15,), ("uniform", 200, 600), 8, 1),
+    ("tree_short", 8, (0, 3, 8), ("uniform", 0, 20), 8, 2),
+    ("tree_split", 4, (4, 8), ("uniform", 900, 2500), 8, 1),
+]
+
+
+@pytest.mark.parametrize("plan", [0, 1])
+@pytest.mark.parametrize("case", TREE_CASES, ids=[c[0] for c in TREE_CASES])
+def test_tree_attention_matches_oracle(sv, oracle, case, plan):
+    name, B, gammas, ctx, Hq, Hkv = case
+    cfg = wl.VerifyConfig(name, 61, B, gammas, ctx, Hq, Hkv, 64, 64, sigma_qkv=1.0)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    rng = np.random.default_rng(len(name))
+    parent = _random_parents(rng, b["gammas"].numpy())
+    sv.spec_set_tuning("attn_plan", 1 if plan else 2)
+    if name == "tree_split":
+        sv.spec_set_tuning("attn_chunk", 256)
+    try:
+        step = _step(b, cfg)
+        step.attn_out.fill_(7.0)
+        sv.spec_verify_attn_tree(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"],
+                                 torch.from_numpy(parent).cuda(), step.attn_out, step.lse, b["max_kv_len"],
+                                 b["gamma_max"] + 1, b["scale"], step.status, step.attn_ws)
+        torch.cuda.synchronize()
+    finally:
+        sv.spec_set_tuning("attn_plan", 0)
+        sv.spec_set_tuning("attn_chunk", 0)
+    ref, ref_lse = oracle.verify_attn_tree(wl.bf16_bits(b["q"]), wl.bf16_bits(b["k_cache"]), wl.bf16_bits(b["v_cache"]),
+                                           b["page_table"].cpu().numpy(), b["seq_lens"].cpu().numpy(),
+                                           b["qo_indptr"].cpu().numpy(), parent, b["scale"], want_lse=True)
+    _close(step.attn_out.float().cpu().numpy(), ref, name, sharp=True)
+    np.testing.assert_allclose(step.lse.cpu().numpy(), ref_lse, rtol=2e-3, atol=2e-3)
+    assert int(step.status.cpu()) == 0
+
+
+def test_tree_attention_chain_parents_and_bad_trees(sv, oracle):
+    cfg = wl.VerifyConfig("treechain", 62, 4, (3, 6), ("uniform", 50, 400), 8, 1, 64, 64, sigma_qkv=1.0)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    gam = b["gammas"].numpy()
+    chain = np.concatenate([np.arange(-1, g, dtype=np.int32) for g in gam])
+    step = _step(b, cfg)
+    plain = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"]).clone()
+    lse_plain = step.lse.clone()
+    sv.spec_verify_attn_tree(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"],
+                             torch.from_numpy(chain).cuda(), step.attn_out, step.lse, b["max_kv_len"], b["gamma_max"] + 1,
+                             b["scale"], step.status, step.attn_ws)
+    torch.cuda.synchronize()
+    assert torch.equal(step.attn_out, plain) and torch.equal(step.lse, lse_plain)     # the chain is the degenerate tree
+    bad = chain.copy()
+    qo = b["qo_indptr"].cpu().numpy()
+    bad[qo[2] + 1] = 3                                                                 # a parent after its child, request 2
+    step.attn_out.fill_(5.0)
+    sv.spec_verify_attn_tree(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"],
+                             torch.from_numpy(bad).cuda(), step.attn_out, step.lse, b["max_kv_len"], b["gamma_max"] + 1,
+                             b["scale"], step.status, step.attn_ws)
+    torch.cuda.synchronize()
+    assert int(step.status.cpu()) & sv.FLAG_BAD_TREE
+    assert (step.attn_out[qo[2]:qo[3]].float() == 5.0).all()                           # skipped
+    keep = np.r_[0:qo[2], qo[3]:qo[4]]
+    assert torch.equal(step.attn_out[keep], plain[keep])
+
+
+def test_tree_acceptance_and_commit_are_bit_exact(sv, oracle):
+    rng = np.random.default_rng(63)
+    cfg = wl.VerifyConfig("treeacc", 63, 40, (0, 3, 6, 12), ("uniform", 0, 300), 8, 2, 64, 64)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    gam = b["gammas"].numpy()
+    qo = b["qo_indptr"].cpu().numpy()
+    B, M, V, gmax = len(gam), int(qo[-1]), 4099, int(gam.max())
+    parent = _random_parents(rng, gam)
+    logits = rng.normal(0, 1, (M, V)).astype(np.float32)
+    am = logits.argmax(1)
+    tokens = rng.integers(0, V, M).astype(np.int32)
+    for i in range(B):                                    # let most nodes carry their parent's argmax: deep walks
+        for j in range(1, gam[i] + 1):
+            if rng.random() < 0.7:
+                tokens[qo[i] + j] = am[qo[i] + parent[qo[i] + j]]
+    dev = lambda a: torch.from_numpy(a).cuda()
+    ws = torch.empty(max(256, sv.spec_accept_workspace_bytes(B, M, V, gmax)), dtype=torch.uint8, device="cuda")
+    al = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    ot = torch.full((B, gmax + 1), -9, dtype=torch.int32, device="cuda")
+    pth = torch.full((B, gmax + 1), -9, dtype=torch.int32, device="cuda")
+    rb = torch.full((B,), 9, dtype=torch.uint8, device="cuda")
+    st = torch.full((4,), -9, dtype=torch.int32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sv.spec_accept_tree(dev(logits), dev(tokens), dev(parent), b["qo_indptr"], al, ot, pth, rb, st, gmax, status, ws)
+    torch.cuda.synchronize()
+    ref = oracle.accept_tree(logits, tokens, parent, qo, gmax)
+    assert np.array_equal(al.cpu().numpy(), ref["accept_len"]) and np.array_equal(ot.cpu().numpy(), ref["out_tokens"])
+    assert np.array_equal(pth.cpu().numpy(), ref["path"]) and np.array_equal(rb.cpu().numpy(), ref["rollback"])
+    assert st.cpu().numpy().tolist() == [int(ref["rollback"].sum()), int((ref["accept_len"] + 1).sum()), B, 0]
+    assert int(status.cpu()) == 0 and ref["accept_len"].max() >= 3
+    # commit: gather the accepted paths, then the page bookkeeping
+    kc, vc = wl.bf16_bits(b["k_cache"]).copy(), wl.bf16_bits(b["v_cache"]).copy()
+    pt, sl = b["page_table"].cpu().numpy().copy(), b["seq_lens"].cpu().numpy().copy()
+    fl, fc = b["free_list"].cpu().numpy().copy(), b["free_count"].cpu().numpy().copy()
+    oracle.kv_commit_tree(kc, vc, pt, sl, qo, ref["accept_len"], ref["path"], fl, fc, 16)
+    sv.spec_kv_commit_tree(b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], al, pth,
+                           b["free_list"], b["free_count"], status)
+    torch.cuda.synchronize()
+    assert np.array_equal(wl.bf16_bits(b["k_cache"]), kc) and np.array_equal(wl.bf16_bits(b["v_cache"]), vc)
+    assert np.array_equal(b["page_table"].cpu().numpy(), pt) and np.array_equal(b["seq_lens"].cpu().numpy(), sl)
+    assert int(b["free_count"].cpu()) == int(fc[0])
+    assert np.array_equal(b["free_list"].cpu().numpy()[:int(fc[0])], fl[:int(fc[0])])
+    assert int(status.cpu()) == 0
+
+
+def test_tree_acceptance_flags_bad_trees_and_tokens(sv, oracle):
+    V = 1000
+    qo = np.array([0, 3, 6, 9], np.int32)
+    parent = np.array([-1, 0, 0, -1, 2, 0, -1, 0, 1], np.int32)      # request 1: node 1's parent is after it
+    tokens = np.array([0, 4, 4, 0, 1, 2, 0, V + 5, 3], np.int32)       # request 2: a token outside the vocabulary
+    logits = np.random.default_rng(1).normal(0, 1, (9, V)).astype(np.float32)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    ws = torch.empty(max(256, sv.spec_accept_workspace_bytes(3, 9, V, 2)), dtype=torch.uint8, device="cuda")
+    al = torch.full((3,), -9, dtype=torch.int32, device="cuda")
+    ot = torch.full((3, 3), -9, dtype=torch.int32, device="cuda")
+    pth = torch.full((3, 3), -9, dtype=torch.int32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sv.spec_accept_tree(dev(logits), dev(tokens), dev(parent), dev(qo), al, ot, pth, None, None, 2, status, ws)
+    torch.cuda.synchronize()
+    ref = oracle.accept_tree(logits, tokens, parent, qo, 2)
+    assert np.array_equal(al.cpu().numpy(), ref["accept_len"]) and np.array_equal(ot.cpu().numpy(), ref["out_tokens"])
+    assert np.array_equal(pth.cpu().numpy(), ref["path"])
+    assert int(status.cpu()) & sv.FLAG_BAD_TREE and int(status.cpu()) & sv.FLAG_BAD_TOKEN
+    assert ot.cpu().numpy()[1].tolist() == [-1, -1, -1] and ot.cpu().numpy()[2].tolist() == [-1, -1, -1]
+
+
 # --------------------------------------------------------------------------- whole step
 def _run_step(sv, oracle, cfg, stochastic, fused=False):
     b = wl.make_batch(cfg, device="cuda")
