@@ -40,6 +40,20 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the device's copy of the code) and
+// again whenever a launch needs more.  `granted` is the caller's static table, one slot per device ordinal.
+constexpr int kMaxDevices = 64;
+inline int ensure_dynamic_lds(const void* kernel, size_t bytes, size_t (&granted)[kMaxDevices], const char* who)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+    if (granted[dev] >= bytes) return SPEC_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        return fail(SPEC_EHIP, "%s: cannot reserve %zu bytes of LDS", who, bytes);
+    granted[dev] = bytes;
+    return SPEC_OK;
+}
+
 // fp32 -> bf16, round to nearest even (inputs here are finite)
 __device__ inline uint32_t f32_to_bf16_bits(float f)
 {

@@ -473,13 +473,8 @@ static int launch_big(const uint16_t* a, const uint16_t* w, float* c, int M, int
 {
     constexpr int BM = 64 * TMW;
     const size_t smem = (size_t)kBigStages * (BM + kBigBN) * kBigBK * 2;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_big_kernel<TMW, NW>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
-        configured = true;
-    }
+    static size_t granted[kMaxDevices] = {};
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_big_kernel<TMW, NW>), smem, granted, "spec_lm_head")) return rc;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (V + kBigBN - 1) / kBigBN;
     const long grid = (long)((tiles_n + 7) / 8) * 8 * tiles_m;
     hipLaunchKernelGGL((lm_head_big_kernel<TMW, NW>), dim3((unsigned)grid), dim3(64 * NW), smem, s, a, w, c, M, H, V, tiles_m, tiles_n);
@@ -615,13 +610,8 @@ static int launch_big2(const uint16_t* a, const uint16_t* w, float* c, int M, in
 {
     constexpr int BM = 64 * TMW;
     const size_t smem = 2 * (size_t)(BM + kBigBN) * kB2BK * 2;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_big2_kernel<TMW, NW>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
-        configured = true;
-    }
+    static size_t granted[kMaxDevices] = {};
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_big2_kernel<TMW, NW>), smem, granted, "spec_lm_head")) return rc;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (V + kBigBN - 1) / kBigBN;
     const long grid = (long)((tiles_n + 7) / 8) * 8 * tiles_m;
     hipLaunchKernelGGL((lm_head_big2_kernel<TMW, NW>), dim3((unsigned)grid), dim3(64 * NW), smem, s, a, w, c, M, H, V, tiles_m, tiles_n);
@@ -664,13 +654,8 @@ static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, 
 {
     constexpr int BM = (TM + MS - 1) / MS * MS * 16;
     const size_t smem = 2 * (size_t)BM * kHPitch;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM, MS, RS, PAIR, STATS>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return fail(SPEC_EHIP, "spec_lm_head: cannot reserve %zu bytes of LDS", smem);
-        configured = true;
-    }
+    static size_t granted[kMaxDevices] = {};
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM, MS, RS, PAIR, STATS>), smem, granted, "spec_lm_head")) return rc;
     int cols, grid;
     skinny_geometry(V, &cols, &grid);
     const int ppw = (cols + kPassCols - 1) / kPassCols;

@@ -707,13 +707,9 @@ template <int NR, int NW, int NBUF, bool FINAL>
 static int launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t s)
 {
     const size_t smem = attn_smem_bytes(NR, NW, NBUF, p.chunk_target < p.max_kv_len ? p.chunk_target : p.max_kv_len);
-    static size_t configured = 0;
-    if (configured < smem) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&verify_attn_kernel<NR, NW, NBUF, FINAL>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return fail(SPEC_EHIP, "spec_verify_attn: cannot reserve %zu bytes of LDS", smem);
-        configured = smem;
-    }
+    static size_t granted[kMaxDevices] = {};
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&verify_attn_kernel<NR, NW, NBUF, FINAL>), smem, granted,
+                                    "spec_verify_attn")) return rc;
     hipLaunchKernelGGL((verify_attn_kernel<NR, NW, NBUF, FINAL>), grid, dim3(NW * 64), smem, s, p);
     return SPEC_OK;
 }
