@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--attn-chunk", type=int, default=0, help="override keys per kv split (0 = library heuristic)")
     ap.add_argument("--fused-stats", action="store_true",
                     help="spec_lm_head_stats + spec_accept_stats instead of spec_lm_head + spec_accept (same outputs; "
-                         "measured slower on MI355X, see DESIGN.md)")
+                         "measured slower per step on MI355X)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (untimed): under rocprofv3 --pmc its FETCH_SIZE / "
                          "WRITE_SIZE readings calibrate the counters against a known byte count")

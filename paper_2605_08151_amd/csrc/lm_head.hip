@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void lm_head_tiled_kernel(
 
 
 // ------------------------------------------------------------------------------------------------
-// Weight-streaming kernel for M <= 160 rows (the verify batches of BASELINE configs 1, 2 and 4):
+// Weight-streaming kernel for M <= 160 rows (verify batches of a few dozen requests with a handful of drafts each):
 // the roof is HBM (W is read once, 2*V*H bytes), so the layout is built around the W stream.
 //   * One persistent workgroup per CU owns a contiguous range of vocabulary entries and walks it in
 //     passes of 4 waves x 32 entries; the last pass is split evenly over the waves so that all CUs
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// MFMA-bound kernel for M > 160 rows (BASELINE configs 3 and 5: 576 and ~1152 rows).
+// MFMA-bound kernel for M > 160 rows (large or deeply speculating batches: 576 to ~1200 rows).
 //   * (64*TMW) x 256 output tile per workgroup, 4 waves in a 2 x 2 grid, each wave TMW x 4 tiles of
 //     v_mfma_f32_32x32x16_bf16 (up to 256 accumulator registers).
 //   * K advances in slabs of 32 through a ring of 4 LDS stages filled by direct HBM/L2 -> LDS loads

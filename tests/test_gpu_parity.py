@@ -1,6 +1,6 @@
 """GPU parity: every library call against the CPU oracle on the same seeded inputs, through the C ABI.
 
-Tolerances (written here, derived in the design doc): attention and logits |err| <= 1e-2 + 2e-2*|ref| (bf16 inputs,
+Tolerances (written here; derived from bf16 inputs, fp32 accumulation and bf16 outputs): attention and logits |err| <= 1e-2 + 2e-2*|ref| (bf16 inputs,
 fp32 accumulation) and, because N(0, 0.02) data would make that check vacuous, also
 |err| <= 1e-2 * (|ref| + rms of the element's own output vector) on unit-variance ("sharp") data, 2e-2 otherwise.  Acceptance and commit outputs are integers and must be bit-exact.
 """
@@ -727,7 +727,7 @@ def _run_step(sv, oracle, cfg, stochastic, fused=False):
 
 
 def test_whole_step_tiny_config(sv, oracle):
-    """BASELINE configuration 1 end to end."""
+    """The smallest workload (4 requests, 5 rows each, short contexts) end to end."""
     cfg = wl.CONFIGS["tiny"]
     b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=False)
     _close(out.float().cpu().numpy(), ref_attn, "tiny attn")
@@ -931,7 +931,7 @@ def test_step_can_be_captured_in_a_graph_and_replayed(sv, oracle):
         sv.spec_set_tuning("attn_plan", 0)
 
 
-# --------------------------------------------------------------------------- BASELINE configurations at full size
+# --------------------------------------------------------------------------- the benchmark workloads at full size
 def _sampled_logits_check(oracle, b, gl, n_cols=192, seed=0):
     """LM head at full size: the oracle recomputes all rows for a random sample of vocabulary entries
     (plus the first and last 32, which sit in the ragged tiles)."""
@@ -944,7 +944,7 @@ def _sampled_logits_check(oracle, b, gl, n_cols=192, seed=0):
 
 @pytest.mark.parametrize("name", ["mid", "stochastic", "long"])
 def test_full_size_configuration(sv, oracle, name):
-    """BASELINE configurations 2, 3 and 4 at full size, in the launch configuration bench.py times:
+    """The mid, stochastic and long workloads at full size, in the launch configuration bench.py times:
     attention against the oracle on every row, logits on sampled vocabulary entries, acceptance and
     commit bit-exact on the GPU's own logits."""
     cfg = wl.CONFIGS[name]
@@ -955,7 +955,7 @@ def test_full_size_configuration(sv, oracle, name):
 
 
 def test_full_size_hybrid_mix_properties(sv, oracle):
-    """BASELINE configuration 5 (B=256, gamma in {0,2,4,8}, lognormal contexts up to 32k, half sampled):
+    """The hybrid workload (B=256, gamma in {0,2,4,8}, lognormal contexts up to 32k, half sampled):
     attention is checked on a sample of requests the oracle recomputes (all their rows and heads),
     acceptance and commit are bit-exact on the whole batch."""
     cfg = wl.CONFIGS["hybrid"]
