@@ -622,7 +622,7 @@ int g_lm_kernel_waves = 8;  // benchmark hook: waves per workgroup of the MFMA-b
 int g_lm_kernel = 0;   // benchmark hook: 0 = automatic, 1 = weight-streaming, 2 = MFMA-bound with direct loads, 3 = plain tiled,
                        // 8 = MFMA-bound with register staging (the automatic choice for M > 160),
                        // 4 = weight-streaming with 8 waves (4 x 2) and a 2-slab ring, 5/6/7 = 4 waves with
-                       // 2-slab ring / 4-slab ring + paired refills / 2-slab ring + paired refills (the default)
+                       // 4-slab ring / 4-slab ring + paired refills / 2-slab ring + paired refills (the default)
 
 static int device_cu_count()
 {
@@ -672,7 +672,7 @@ static int launch_skinny_auto(const uint16_t* a, const uint16_t* w, float* c, in
     // paired refills ~347 us, with a 4-slab ring and single refills ~363 us, 8 waves (two wave rows re-reading
     // the same W rows) with a 2-slab ring ~470 us
     if (g_lm_kernel == 4) return launch_skinny<TM, 2, 2>(a, w, c, M, H, V, s);
-    if (g_lm_kernel == 5) return launch_skinny<TM, 1, 2>(a, w, c, M, H, V, s);
+    if (g_lm_kernel == 5) return launch_skinny<TM, 1, 4>(a, w, c, M, H, V, s);
     if (g_lm_kernel == 6) return launch_skinny<TM, 1, 4, 1>(a, w, c, M, H, V, s);
     if (g_lm_kernel == 7) return launch_skinny<TM, 1, 2, 1>(a, w, c, M, H, V, s);
     return launch_skinny<TM, 1, 2, 1>(a, w, c, M, H, V, s);
@@ -681,7 +681,9 @@ static int launch_skinny_auto(const uint16_t* a, const uint16_t* w, float* c, in
 static bool skinny_applies(int M, int H)
 {
     const int force = g_lm_kernel;
-    return (force == 0 || force == 1 || force >= 4) && M <= 160 && H % (4 * kSlab) == 0;
+    // the register ring holds 2 slabs of 128 k (4 in the variants 5 and 6): H must be a whole number of rings
+    const int ring = (force == 5 || force == 6) ? 4 : 2;
+    return (force == 0 || force == 1 || force >= 4) && force != 8 && M <= 160 && H % (ring * kSlab) == 0;
 }
 
 }  // namespace specv

@@ -209,7 +209,7 @@ def test_host_side_rejections(sv):
 
 
 # --------------------------------------------------------------------------- LM head
-@pytest.mark.parametrize("M,H,V,std", [(20, 1024, 32000, 0.02), (7, 192, 1013, 1.0), (160, 512, 4100, 1.0),
+@pytest.mark.parametrize("M,H,V,std", [(20, 1024, 32000, 0.02), (7, 192, 1013, 1.0), (160, 512, 4100, 1.0), (45, 768, 3001, 1.0),
                                        (300, 256, 777, 1.0), (1, 64, 5, 1.0), (64, 128, 128, 1.0)])
 def test_lm_head_matches_oracle(sv, oracle, M, H, V, std):
     g = torch.Generator(device="cuda").manual_seed(M * 7 + V)
