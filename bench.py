@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--fused-stats", action="store_true",
                     help="spec_lm_head_stats + spec_accept_stats instead of spec_lm_head + spec_accept (same outputs; "
                          "measured slower per step on MI355X)")
+    ap.add_argument("--lm-weights", choices=("auto", "packed", "rowmajor"), default="auto",
+                    help="layout of the vocabulary matrix: packed (spec_lm_head_packed; re-laid once before the timed "
+                         "region, as at model load) or rowmajor (spec_lm_head); auto = packed when the batch has at "
+                         "most 160 rows, the weight-streaming regime the packed layout is built for")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (untimed): under rocprofv3 --pmc its FETCH_SIZE / "
                          "WRITE_SIZE readings calibrate the counters against a known byte count")
@@ -68,7 +72,11 @@ def main():
     B, M, V, H = b["B"], b["M"], cfg.V, cfg.H
     step = VerifyStep(B, M, cfg.Hq, cfg.Hkv, cfg.D, H, V, b["gamma_max"], b["max_kv_len"])
     qo = b["qo_indptr"]
-    logits = step.lm_head(b["hidden"], b["W"])
+    packed = args.lm_weights == "packed" or (args.lm_weights == "auto" and M <= 160 and H % 256 == 0)
+    if packed and args.fused_stats:
+        sys.exit("bench.py: --fused-stats needs --lm-weights rowmajor")
+    Wp = step.pack_weights(b["W"]) if packed else None      # load-time work, not part of a step
+    logits = step.lm_head_packed(b["hidden"], Wp) if packed else step.lm_head(b["hidden"], b["W"])
     torch.cuda.synchronize()
     stochastic = bool((b["temperature"] > 0).any())
     tokens_g, _ = wl.draft_tokens_greedy(cfg, qo, logits.argmax(1).cpu())
@@ -97,6 +105,8 @@ def main():
         if events: events[1].record()
         if fused:
             step.lm_head_stats(b["hidden"], b["W"])
+        elif packed:
+            step.lm_head_packed(b["hidden"], Wp)
         else:
             step.lm_head(b["hidden"], b["W"])
         if events: events[2].record()
@@ -167,6 +177,7 @@ def main():
         "config": {"workload": f"{cfg.name}: B={B} gamma={sorted(set(b['gammas'].tolist()))} M={M} ctx={cfg.ctx} "
                                f"Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} page={cfg.P} H={H} V={V} "
                                f"temperature={cfg.temperature} seed={cfg.seed}",
+                   "lm_weights": "packed" if packed else "rowmajor",
                    "emitted_tokens_per_step": emitted, "scored_positions_per_step": M,
                    "scored_positions_per_s": M / (ms_per_step * 1e-3), "kv_tokens": kv_tokens},
         "roofline": roofline,

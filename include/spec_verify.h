@@ -72,8 +72,10 @@ int spec_version(void);
  * "lm_kernel" = kernel used by spec_lm_head, 0 = automatic (weight-streaming kernel for M <= 160, MFMA-bound
  * kernel above), 1 = weight-streaming, 2 = MFMA-bound with direct global->LDS loads, 3 = plain tiled,
  * 4..7 = weight-streaming variants (wave count / register-ring depth), 8 = MFMA-bound with register staging;
- * "lm_big_waves" = waves per workgroup of the MFMA-bound kernels, 4 or 8 (default).  A forced kernel that cannot take the shape falls back to the plain
- * tiled one.  Unknown key: SPEC_EINVAL. */
+ * "lm_big_waves" = waves per workgroup of the MFMA-bound kernels, 4 or 8 (default);
+ * "lm_packed_ring" = slabs of 128 k in the W register ring of spec_lm_head_packed, 0 = automatic, 1 or 2;
+ * "lm_packed_waves" = waves per workgroup of spec_lm_head_packed, 4 or 8 (default).
+ * A forced kernel that cannot take the shape falls back to the plain tiled one.  Unknown key: SPEC_EINVAL. */
 int spec_set_tuning(const char* key, int value);
 
 /* ---------------------------------------------------------------------------
@@ -155,6 +157,30 @@ int spec_lm_head_stats_blocks(int M, int H, int V);
 
 int spec_lm_head_stats(const void* hidden, const void* W, float* logits, int M, int H, int V,
                        float* blk_max, int32_t* blk_arg, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * spec_lm_head_pack / spec_lm_head_packed — spec_lm_head (same operation, same
+ * passage, same logits up to fp32 summation order) with the vocabulary matrix
+ * re-laid once, when the model is loaded, into the order the matrix cores read
+ * it, so that the weight stream of a verify batch is a linear read.
+ *   Wp (device, caller-owned, spec_lm_head_packed_bytes(V, H) bytes, 16-byte
+ *   aligned): panels of 16 vocabulary entries; for panel p, k-tile t (32
+ *   consecutive k), lane l in [0, 64), element j in [0, 8):
+ *     Wp[((p * (H/32) + t) * 64 + l) * 8 + j] = W[16 p + l % 16][32 t + 8 (l / 16) + j]
+ *   and 0 where 16 p + l % 16 >= V; ceil(V / 16) panels.
+ *   spec_lm_head_packed_bytes: host arithmetic; 0 for V <= 0 or H <= 0.
+ *   spec_lm_head_pack: W [V, H] bf16 row-major -> Wp; H % 32 == 0 (SPEC_ESHAPE).
+ *   spec_lm_head_packed: hidden [M, H] bf16, logits [M, V] fp32; H % 256 == 0
+ *   (SPEC_ESHAPE otherwise); any M (rows are taken 160 at a time,
+ *   each group streaming Wp once: built for verify batches of M <= 160 rows,
+ *   correct beyond) and any V.
+ * Both are asynchronous on the stream and allocate nothing.
+ * ------------------------------------------------------------------------- */
+size_t spec_lm_head_packed_bytes(int V, int H);
+
+int spec_lm_head_pack(const void* W, void* Wp, int V, int H, void* stream);
+
+int spec_lm_head_packed(const void* hidden, const void* Wp, float* logits, int M, int H, int V, void* stream);
 
 /* ---------------------------------------------------------------------------
  * spec_accept — accepted length and bonus token per request (Method,

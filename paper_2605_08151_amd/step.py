@@ -40,6 +40,16 @@ class VerifyStep:
         sv.spec_lm_head(hidden, W, self.logits)
         return self.logits
 
+    def pack_weights(self, W):
+        """The vocabulary matrix in the layout spec_lm_head_packed reads (done once, when the model is loaded)."""
+        Wp = torch.empty(sv.spec_lm_head_packed_bytes(self.V, self.H) // 2, dtype=torch.bfloat16, device=W.device)
+        sv.spec_lm_head_pack(W, Wp)
+        return Wp
+
+    def lm_head_packed(self, hidden, Wp):
+        sv.spec_lm_head_packed(hidden, Wp, self.logits)
+        return self.logits
+
     def lm_head_stats(self, hidden, W):
         sv.spec_lm_head_stats(hidden, W, self.logits, self.blk_max, self.blk_arg)
         return self.logits

@@ -226,6 +226,74 @@ def test_lm_head_matches_oracle(sv, oracle, M, H, V, std):
     assert np.abs(got - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max()) * math.sqrt(H)
 
 
+def _packed_layout(wbits: np.ndarray) -> np.ndarray:
+    """The packed vocabulary matrix as the header defines it, by index arithmetic on the host."""
+    V, H = wbits.shape
+    panels = (V + 15) // 16
+    padded = np.zeros((panels * 16, H), dtype=np.uint16)
+    padded[:V] = wbits
+    # [panel, entry-in-panel, k-tile, k-group, j] -> [panel, k-tile, k-group, entry-in-panel, j]; lane = 16 * k-group + entry
+    return padded.reshape(panels, 16, H // 32, 4, 8).transpose(0, 2, 3, 1, 4).reshape(-1).copy()
+
+
+@pytest.mark.parametrize("V,H", [(1013, 256), (4096, 512), (5, 32), (16, 64), (3001, 768)])
+def test_lm_head_pack_is_the_documented_permutation(sv, V, H):
+    g = torch.Generator(device="cuda").manual_seed(V + H)
+    W = torch.randn((V, H), generator=g, device="cuda").to(torch.bfloat16)
+    nbytes = sv.spec_lm_head_packed_bytes(V, H)
+    assert nbytes == (V + 15) // 16 * 16 * H * 2
+    Wp = torch.full((nbytes // 2,), 7.0, dtype=torch.bfloat16, device="cuda")
+    sv.spec_lm_head_pack(W, Wp)
+    torch.cuda.synchronize()
+    assert np.array_equal(wl.bf16_bits(Wp), _packed_layout(wl.bf16_bits(W)))
+
+
+@pytest.mark.parametrize("M,H,V,std", [(20, 1024, 32000, 0.02), (7, 256, 1013, 1.0), (160, 512, 4100, 1.0), (45, 768, 3001, 1.0),
+                                       (300, 256, 777, 1.0), (1, 256, 5, 1.0), (64, 256, 128, 1.0), (97, 512, 70001, 1.0),
+                                       (130, 256, 16 * 256 * 16 + 4, 1.0)])
+def test_lm_head_packed_matches_oracle(sv, oracle, M, H, V, std):
+    g = torch.Generator(device="cuda").manual_seed(M * 7 + V)
+    hs, ws = (1.0, 1.0 / math.sqrt(H)) if std == 1.0 else (std, std)
+    hidden = (torch.randn((M, H), generator=g, device="cuda") * hs).to(torch.bfloat16)
+    W = (torch.randn((V, H), generator=g, device="cuda") * ws).to(torch.bfloat16)
+    Wp = torch.empty((sv.spec_lm_head_packed_bytes(V, H) // 2,), dtype=torch.bfloat16, device="cuda")
+    sv.spec_lm_head_pack(W, Wp)
+    logits = torch.full((M, V), 3.0, dtype=torch.float32, device="cuda")
+    sv.spec_lm_head_packed(hidden, Wp, logits)
+    torch.cuda.synchronize()
+    ref = oracle.lm_head(wl.bf16_bits(hidden), wl.bf16_bits(W))
+    got = logits.cpu().numpy()
+    _close(got, ref, f"lm_head_packed {M}x{H}x{V}", sharp=std == 1.0)
+    assert np.abs(got - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max()) * math.sqrt(H)
+    # the launch variants (deeper register ring, 4 waves) add in the same order
+    try:
+        for tun in ({"lm_packed_ring": 2}, {"lm_packed_waves": 4}, {"lm_packed_waves": 4, "lm_packed_ring": 2}):
+            for k, v in tun.items():
+                sv.spec_set_tuning(k, v)
+            again = torch.zeros_like(logits)
+            sv.spec_lm_head_packed(hidden, Wp, again)
+            torch.cuda.synchronize()
+            assert torch.equal(again, logits), tun
+            sv.spec_set_tuning("lm_packed_ring", 0)
+            sv.spec_set_tuning("lm_packed_waves", 8)
+    finally:
+        sv.spec_set_tuning("lm_packed_ring", 0)
+        sv.spec_set_tuning("lm_packed_waves", 8)
+
+
+def test_lm_head_packed_rejects_bad_shapes(sv):
+    hidden = torch.zeros((4, 192), dtype=torch.bfloat16, device="cuda")
+    Wp = torch.zeros((sv.spec_lm_head_packed_bytes(40, 192) // 2,), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sv.SpecError) as e:
+        sv.spec_lm_head_packed(hidden, Wp, torch.zeros((4, 40), dtype=torch.float32, device="cuda"))
+    assert e.value.code == -2
+    with pytest.raises(sv.SpecError) as e:
+        sv.spec_lm_head_pack(torch.zeros((40, 48), dtype=torch.bfloat16, device="cuda"),
+                             torch.zeros((sv.spec_lm_head_packed_bytes(40, 48) // 2,), dtype=torch.bfloat16, device="cuda"))
+    assert e.value.code == -2
+    assert sv.spec_lm_head_packed_bytes(0, 256) == 0
+
+
 # --------------------------------------------------------------------------- acceptance
 def _accept_both(sv, oracle, logits, tokens, dp, temp, seeds, round_, qo, gamma_max):
     B, (M, V) = len(qo) - 1, logits.shape
