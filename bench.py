@@ -38,8 +38,8 @@ def parse():
                          "measured slower per step on MI355X)")
     ap.add_argument("--lm-weights", choices=("auto", "packed", "rowmajor"), default="auto",
                     help="layout of the vocabulary matrix: packed (spec_lm_head_packed; re-laid once before the timed "
-                         "region, as at model load) or rowmajor (spec_lm_head); auto = packed when the batch has at "
-                         "most 160 rows, the weight-streaming regime the packed layout is built for")
+                         "region, as at model load) or rowmajor (spec_lm_head); auto = packed whenever the kernel takes "
+                         "the shape (H a multiple of 256)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (untimed): under rocprofv3 --pmc its FETCH_SIZE / "
                          "WRITE_SIZE readings calibrate the counters against a known byte count")
@@ -72,7 +72,7 @@ def main():
     B, M, V, H = b["B"], b["M"], cfg.V, cfg.H
     step = VerifyStep(B, M, cfg.Hq, cfg.Hkv, cfg.D, H, V, b["gamma_max"], b["max_kv_len"])
     qo = b["qo_indptr"]
-    packed = args.lm_weights == "packed" or (args.lm_weights == "auto" and M <= 160 and H % 256 == 0)
+    packed = args.lm_weights == "packed" or (args.lm_weights == "auto" and H % 256 == 0 and not args.fused_stats)
     if packed and args.fused_stats:
         sys.exit("bench.py: --fused-stats needs --lm-weights rowmajor")
     Wp = step.pack_weights(b["W"]) if packed else None      # load-time work, not part of a step

@@ -73,7 +73,6 @@ int spec_version(void);
  * kernel above), 1 = weight-streaming, 2 = MFMA-bound with direct global->LDS loads, 3 = plain tiled,
  * 4..7 = weight-streaming variants (wave count / register-ring depth), 8 = MFMA-bound with register staging;
  * "lm_big_waves" = waves per workgroup of the MFMA-bound kernels, 4 or 8 (default);
- * "lm_packed_ring" = slabs of 128 k in the W register ring of spec_lm_head_packed, 0 = automatic, 1 or 2;
  * "lm_packed_waves" = waves per workgroup of spec_lm_head_packed, 4 or 8 (default).
  * A forced kernel that cannot take the shape falls back to the plain tiled one.  Unknown key: SPEC_EINVAL. */
 int spec_set_tuning(const char* key, int value);
@@ -171,9 +170,9 @@ int spec_lm_head_stats(const void* hidden, const void* W, float* logits, int M, 
  *   spec_lm_head_packed_bytes: host arithmetic; 0 for V <= 0 or H <= 0.
  *   spec_lm_head_pack: W [V, H] bf16 row-major -> Wp; H % 32 == 0 (SPEC_ESHAPE).
  *   spec_lm_head_packed: hidden [M, H] bf16, logits [M, V] fp32; H % 256 == 0
- *   (SPEC_ESHAPE otherwise); any M (rows are taken 160 at a time,
- *   each group streaming Wp once: built for verify batches of M <= 160 rows,
- *   correct beyond) and any V.
+ *   (SPEC_ESHAPE otherwise); any M (above 160 rows the batch is cut into
+ *   equal row groups that stream the same panels at the same time on one XCD,
+ *   so that HBM still sees Wp once) and any V.
  * Both are asynchronous on the stream and allocate nothing.
  * ------------------------------------------------------------------------- */
 size_t spec_lm_head_packed_bytes(int V, int H);

@@ -17,7 +17,6 @@ extern int g_lm_kernel;
 extern int g_lm_kernel_waves;
 extern int g_attn_plan;
 extern int g_attn_plan_waves;
-extern int g_lm_packed_ring;
 extern int g_lm_packed_waves;
 
 }  // namespace specv
@@ -32,7 +31,6 @@ extern "C" int spec_version(void) { return 1000; }
 //   "lm_big_waves"  waves per workgroup of its MFMA-bound kernels (4 or 8)
 //   "attn_plan"   balanced work list of spec_verify_attn: 0 = automatic, 1 = always, 2 = never
 //   "attn_plan_waves"  work items per CU the list aims at (0 = automatic)
-//   "lm_packed_ring"  slabs of 128 k in the W register ring of spec_lm_head_packed (0 = automatic, 1 or 2)
 //   "lm_packed_waves"  waves per workgroup of spec_lm_head_packed (4 or 8)
 extern "C" int spec_set_tuning(const char* key, int value)
 {
@@ -41,7 +39,6 @@ extern "C" int spec_set_tuning(const char* key, int value)
     if (key && std::strcmp(key, "lm_big_waves") == 0) { specv::g_lm_kernel_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_plan") == 0) { specv::g_attn_plan = value; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_plan_waves") == 0) { specv::g_attn_plan_waves = value; return SPEC_OK; }
-    if (key && std::strcmp(key, "lm_packed_ring") == 0) { specv::g_lm_packed_ring = value; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_packed_waves") == 0) { specv::g_lm_packed_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     return specv::fail(SPEC_EINVAL, "spec_set_tuning: unknown key '%s'", key ? key : "(null)");
 }

@@ -51,13 +51,16 @@ __global__ __launch_bounds__(256) void lm_head_pack_kernel(const uint16_t* __res
 //     in-order queue with loads.
 //   * C^T tiles come out with 4 consecutive vocabulary entries per lane and 16 rows per instruction; they are
 //     turned through LDS so that a store instruction writes whole 128-byte lines (all the wave's entries of a
-//     row, 128 or 256 bytes), and stored nontemporal: nobody reads them before the next kernel.
-// TM: 16-row tiles of hidden (M <= 16 TM); RS: slabs in the W register ring; NW: waves (4 or 8; 16 / NW panels each).
+//     row, 128 or 256 bytes).  With one or two row groups they are stored nontemporal (nobody reads them before the
+//     next kernel; 263 against 280 us at M = 160); with many groups the L2 absorbs the writes better (1351 against
+//     1504 us at M = 1152).
+// TM: 16-row tiles of hidden (M <= 16 TM); RS: slabs in the W register ring; NW: waves (4 or 8; 16 / NW panels each);
+// NT: nontemporal stores of the logits.
 // ------------------------------------------------------------------------------------------------
-template <int TM, int RS, int NW>
+template <int TM, int RS, int NW, bool NT>
 __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
-    const uint16_t* __restrict__ A, const uint16_t* __restrict__ Wp, float* __restrict__ C,
-    int M, int H, int V, int n_panels, int panels_per_wg, bool vec_store)
+    const uint16_t* __restrict__ A_all, const uint16_t* __restrict__ Wp, float* __restrict__ C_all,
+    int M_all, int H, int V, int n_panels, int panels_per_wg, bool vec_store, int groups, int rows_per_group)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int TN = kPkPassPanels / NW;            // panels per wave and pass
@@ -70,7 +73,15 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, l16 = lane & 15, kg = lane >> 4;
-    const int p_begin = blockIdx.x * panels_per_wg;
+    // Workgroup -> (row group, panel range).  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2:
+    // the row groups of one panel range sit on the same XCD and are dispatched together, so that they stream the
+    // same panels at the same time and all but the first read of a panel is an L2 hit.
+    const int xcd = blockIdx.x & 7, dealt = blockIdx.x >> 3;
+    const int group = dealt % groups, range = (dealt / groups) * 8 + xcd;
+    const int M = min(rows_per_group, M_all - group * rows_per_group);              // >= 1 by the host's choice of groups
+    const uint16_t* __restrict__ A = A_all + (size_t)group * rows_per_group * H;
+    float* __restrict__ C = C_all + (size_t)group * rows_per_group * V;
+    const int p_begin = range * panels_per_wg;
     const int p_end = min(n_panels, p_begin + panels_per_wg);
     if (p_begin >= p_end) return;
     const int n_own = p_end - p_begin;
@@ -212,10 +223,9 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
                 for (int q = 0; q < 16 / kRowsPerStore; ++q) {
                     const int prow = q * kRowsPerStore + srow, row = tm * 16 + prow;
                     const f32x4 v = *reinterpret_cast<const f32x4*>(patch + prow * kPatchPitch + scol * 4);
-                    // whole lines that nobody reads before the next kernel: streamed past the L2
                     if (row < M && col_ok) {
                         f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<unsigned char*>(C) + off);
-                        __builtin_nontemporal_store(v, dst);
+                        if constexpr (NT) __builtin_nontemporal_store(v, dst); else *dst = v;
                     }
                     off += row_step;                  // one running byte offset (M * V * 4 < 2^32 per launch) instead of
                     asm volatile("" : "+v"(off));     // one row address per store kept alive across the whole pass
@@ -240,37 +250,36 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
 }
 
 int g_lm_packed_waves = 8;     // benchmark hook: waves per workgroup of the packed kernel (4 or 8)
-int g_lm_packed_ring = 0;   // benchmark hook: slabs in the W register ring of the packed kernel, 0 = automatic (1)
 
-template <int TM, int RS, int NW>
-static int launch_packed(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, hipStream_t s)
+template <int TM, int RS, int NW, bool NT>
+static int launch_packed(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, int groups, hipStream_t s)
 {
     constexpr int BM = TM * 16;
     const size_t smem = 2 * (size_t)BM * kPkHPitch + NW * 16 * (kPkPassPanels / NW * 64 + 16);
     static size_t granted[kMaxDevices] = {};
-    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_packed_kernel<TM, RS, NW>), smem, granted, "spec_lm_head_packed")) return rc;
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_packed_kernel<TM, RS, NW, NT>), smem, granted, "spec_lm_head_packed")) return rc;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         cus = 256;
+    // panel ranges: a multiple of 8 (one per XCD and step of the dealing), as many as there are CUs per row group
     const int n_panels = (V + 15) / 16;
-    const int per_wg = (n_panels + cus - 1) / cus;
-    const int grid = (n_panels + per_wg - 1) / per_wg;
+    int ranges = max(8, cus / groups / 8 * 8);
+    const int per_range = (n_panels + ranges - 1) / ranges;
+    ranges = ((n_panels + per_range - 1) / per_range + 7) / 8 * 8;       // trailing ranges without panels are dropped, 8 at a time
     const bool vec_store = (V % 4 == 0);
-    hipLaunchKernelGGL((lm_head_packed_kernel<TM, RS, NW>), dim3(grid), dim3(64 * NW), smem, s, a, wp, c, M, H, V, n_panels, per_wg, vec_store);
+    hipLaunchKernelGGL((lm_head_packed_kernel<TM, RS, NW, NT>), dim3(ranges * groups), dim3(64 * NW), smem, s, a, wp, c, M, H, V, n_panels,
+                       per_range, vec_store, groups, BM);
     return SPEC_OK;
 }
 
 template <int TM>
-static int launch_packed_auto(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, hipStream_t s)
+static int launch_packed_auto(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, int groups, hipStream_t s)
 {
-    // measured on MI355X at M = 160, V = 151936 inside the whole verify step: 8 waves 287 us, 4 waves 297 us; a
-    // 2-slab ring is 5 us slower with either; at M = 40 all variants take 218 us
-    if (g_lm_packed_waves == 4) {
-        if (g_lm_packed_ring == 2) return launch_packed<TM, 2, 4>(a, wp, c, M, H, V, s);
-        return launch_packed<TM, 1, 4>(a, wp, c, M, H, V, s);
-    }
-    if (g_lm_packed_ring == 2) return launch_packed<TM, 2, 8>(a, wp, c, M, H, V, s);
-    return launch_packed<TM, 1, 8>(a, wp, c, M, H, V, s);
+    // measured on MI355X at M = 160, V = 151936 inside the whole verify step: 8 waves 287 us, 4 waves 297 us (a 2-slab
+    // W ring is 5 us slower with either); at M = 40 both take 218 us; at M = 576 and 1152 8 waves are 5 % ahead
+    if (g_lm_packed_waves == 4) return launch_packed<TM, 1, 4, true>(a, wp, c, M, H, V, groups, s);
+    if (groups > 2) return launch_packed<TM, 1, 8, false>(a, wp, c, M, H, V, groups, s);
+    return launch_packed<TM, 1, 8, true>(a, wp, c, M, H, V, groups, s);
 }
 
 }  // namespace specv
@@ -311,19 +320,22 @@ extern "C" int spec_lm_head_packed(const void* hidden, const void* Wp, float* lo
         return fail(SPEC_ESHAPE, "spec_lm_head_packed: V=%d is beyond the 32-bit row offsets of the kernel", V);
     hipStream_t s = (hipStream_t)stream;
     const uint16_t* wp = (const uint16_t*)Wp;
-    // more rows than one launch holds: the rows are taken in groups, each streaming W once
-    for (int r0 = 0; r0 < M; r0 += kPkMaxRows) {
-        const int m = min(kPkMaxRows, M - r0);
-        const uint16_t* a = (const uint16_t*)hidden + (size_t)r0 * H;
-        float* c = logits + (size_t)r0 * V;
-        int rc;
-        if (m <= 32) rc = launch_packed_auto<2>(a, wp, c, m, H, V, s);
-        else if (m <= 64) rc = launch_packed_auto<4>(a, wp, c, m, H, V, s);
-        else if (m <= 96) rc = launch_packed_auto<6>(a, wp, c, m, H, V, s);
-        else if (m <= 128) rc = launch_packed_auto<8>(a, wp, c, m, H, V, s);
-        else rc = launch_packed_auto<10>(a, wp, c, m, H, V, s);
-        if (rc != SPEC_OK) return rc;
-        if (int rc2 = check_launch("spec_lm_head_packed")) return rc2;
+    // More rows than a workgroup holds: the rows are cut into equal groups of at most 160 (a multiple of 16 each), and
+    // the grid is groups x panel ranges.  HBM still sees W once; the other groups read it from the L2.
+    const int groups = (M + kPkMaxRows - 1) / kPkMaxRows;
+    const int tm = ((M + groups - 1) / groups + 15) / 16;               // 16-row tiles per group, 1 .. 10
+    const uint16_t* a = (const uint16_t*)hidden;
+    int rc;
+    switch (tm) {
+        case 1: case 2: rc = launch_packed_auto<2>(a, wp, logits, M, H, V, groups, s); break;
+        case 3: case 4: rc = launch_packed_auto<4>(a, wp, logits, M, H, V, groups, s); break;
+        case 5: case 6: rc = launch_packed_auto<6>(a, wp, logits, M, H, V, groups, s); break;
+        case 7: rc = launch_packed_auto<7>(a, wp, logits, M, H, V, groups, s); break;
+        case 8: rc = launch_packed_auto<8>(a, wp, logits, M, H, V, groups, s); break;
+        case 9: rc = launch_packed_auto<9>(a, wp, logits, M, H, V, groups, s); break;
+        default: rc = launch_packed_auto<10>(a, wp, logits, M, H, V, groups, s); break;
     }
+    if (rc != SPEC_OK) return rc;
+    if (int rc2 = check_launch("spec_lm_head_packed")) return rc2;
     return SPEC_OK;
 }
