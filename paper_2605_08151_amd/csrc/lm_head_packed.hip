@@ -18,7 +18,6 @@ namespace specv {
 
 constexpr int kPkSlab = 128;                   // k per hidden slab in LDS
 constexpr int kPkHPitch = kPkSlab * 2 + 16;    // bytes per hidden row in LDS (272: 16 rows -> 16 bank groups)
-constexpr int kPkPassPanels = 16;              // panels per workgroup pass (256 vocabulary entries)
 constexpr int kPkMaxRows = 160;                // rows of hidden per launch
 
 __global__ __launch_bounds__(256) void lm_head_pack_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ Wp,
@@ -55,20 +54,20 @@ __global__ __launch_bounds__(256) void lm_head_pack_kernel(const uint16_t* __res
 //     next kernel; 263 against 280 us at M = 160); with many groups the L2 absorbs the writes better (1351 against
 //     1504 us at M = 1152).
 // TM: 16-row tiles of hidden (M <= 16 TM); RS: slabs in the W register ring; NW: waves (4 or 8; 16 / NW panels each);
-// NT: nontemporal stores of the logits.
+// NT: nontemporal stores of the logits; TN: panels per wave and pass (2 or 4: a pass is 16 NW TN entries wide).
 // ------------------------------------------------------------------------------------------------
-template <int TM, int RS, int NW, bool NT>
+template <int TM, int RS, int NW, bool NT, int TN>
 __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     const uint16_t* __restrict__ A_all, const uint16_t* __restrict__ Wp, float* __restrict__ C_all,
     int M_all, int H, int V, int n_panels, int panels_per_wg, bool vec_store, int groups, int rows_per_group)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int TN = kPkPassPanels / NW;            // panels per wave and pass
+    constexpr int kPassPanels = NW * TN;              // panels per workgroup pass
     constexpr int kThreads = 64 * NW;
     constexpr int BM = TM * 16;                       // hidden rows staged in LDS (rows >= M repeat row M-1)
     constexpr int H_LOADS = (BM * 16 + kThreads - 1) / kThreads;   // 16-byte chunks of a hidden slab per thread
     constexpr int kRing = 4 * RS;
-    constexpr int kHfAhead = 4;
+    constexpr int kHfAhead = 4;                       // (8 is slower: 340 against 325 us at M = 160)
     constexpr int U = RS % 2 ? 2 * RS : RS;           // slabs per unrolled step: even, so that buffer parities are static
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -85,7 +84,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     const int p_end = min(n_panels, p_begin + panels_per_wg);
     if (p_begin >= p_end) return;
     const int n_own = p_end - p_begin;
-    const int npass = (n_own + kPkPassPanels - 1) / kPkPassPanels;
+    const int npass = (n_own + kPassPanels - 1) / kPassPanels;
 
     f32x4 acc[TN][TM];
 #pragma unroll
@@ -98,7 +97,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     int wave_p0 = 0, wave_np = 0;
     auto open_pass = [&](int pass) {                  // the wave's panels of a pass and their stream pointers
         const int lo = p_begin + (int)((long)pass * n_own / npass);
-        const int hi = p_begin + (int)((long)(pass + 1) * n_own / npass);      // 1 <= hi - lo <= 16
+        const int hi = p_begin + (int)((long)(pass + 1) * n_own / npass);      // 1 <= hi - lo <= kPassPanels
         const int m = hi - lo;
         wave_p0 = lo + wave * m / NW;
         wave_np = lo + (wave + 1) * m / NW - wave_p0; // 0 .. TN; wave_p0 < hi is a panel of the matrix either way
@@ -179,7 +178,11 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
                     if (i + kHfAhead < 4 * TM) hfq[i % kHfAhead] = hfrag(i + kHfAhead);
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn)
-                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wreg[tn][par * 4 + c]), h,
+                        // wave-uniform: a panel slot the wave does not own costs no MFMA.  The chip is power-limited under
+                        // random bf16 operands, so the skipped work raises the clock for everything else (M = 160: 279
+                        // against 295 us); with one wave per SIMD the branches cost more than they save (339 us).
+                        if (NW == 4 || tn == 0 || tn < wave_np)
+                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wreg[tn][par * 4 + c]), h,
                                                                               acc[tn][tm], 0, 0, 0);
                     if (tm == TM - 1) {
                         if (c & 1) {                  // the chunk pair just consumed is requested again, RS slabs further
@@ -249,15 +252,16 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     }
 }
 
+int g_lm_packed_wide = 0;      // benchmark hook: 512-entry passes for M <= 160 (0 = automatic, 1 = always, 2 = never)
 int g_lm_packed_waves = 8;     // benchmark hook: waves per workgroup of the packed kernel (4 or 8)
 
-template <int TM, int RS, int NW, bool NT>
+template <int TM, int RS, int NW, bool NT, int TN>
 static int launch_packed(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, int groups, hipStream_t s)
 {
     constexpr int BM = TM * 16;
-    const size_t smem = 2 * (size_t)BM * kPkHPitch + NW * 16 * (kPkPassPanels / NW * 64 + 16);
+    const size_t smem = 2 * (size_t)BM * kPkHPitch + NW * 16 * (TN * 64 + 16);
     static size_t granted[kMaxDevices] = {};
-    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_packed_kernel<TM, RS, NW, NT>), smem, granted, "spec_lm_head_packed")) return rc;
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_packed_kernel<TM, RS, NW, NT, TN>), smem, granted, "spec_lm_head_packed")) return rc;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         cus = 256;
@@ -267,7 +271,7 @@ static int launch_packed(const uint16_t* a, const uint16_t* wp, float* c, int M,
     const int per_range = (n_panels + ranges - 1) / ranges;
     ranges = ((n_panels + per_range - 1) / per_range + 7) / 8 * 8;       // trailing ranges without panels are dropped, 8 at a time
     const bool vec_store = (V % 4 == 0);
-    hipLaunchKernelGGL((lm_head_packed_kernel<TM, RS, NW, NT>), dim3(ranges * groups), dim3(64 * NW), smem, s, a, wp, c, M, H, V, n_panels,
+    hipLaunchKernelGGL((lm_head_packed_kernel<TM, RS, NW, NT, TN>), dim3(ranges * groups), dim3(64 * NW), smem, s, a, wp, c, M, H, V, n_panels,
                        per_range, vec_store, groups, BM);
     return SPEC_OK;
 }
@@ -277,9 +281,9 @@ static int launch_packed_auto(const uint16_t* a, const uint16_t* wp, float* c, i
 {
     // measured on MI355X at M = 160, V = 151936 inside the whole verify step: 8 waves 287 us, 4 waves 297 us (a 2-slab
     // W ring is 5 us slower with either); at M = 40 both take 218 us; at M = 576 and 1152 8 waves are 5 % ahead
-    if (g_lm_packed_waves == 4) return launch_packed<TM, 1, 4, true>(a, wp, c, M, H, V, groups, s);
-    if (groups > 2) return launch_packed<TM, 1, 8, false>(a, wp, c, M, H, V, groups, s);
-    return launch_packed<TM, 1, 8, true>(a, wp, c, M, H, V, groups, s);
+    if (g_lm_packed_waves == 4) return launch_packed<TM, 1, 4, true, 4>(a, wp, c, M, H, V, groups, s);
+    if (groups > 2) return launch_packed<TM, 1, 8, false, 2>(a, wp, c, M, H, V, groups, s);
+    return launch_packed<TM, 1, 8, true, 2>(a, wp, c, M, H, V, groups, s);
 }
 
 }  // namespace specv
@@ -322,10 +326,22 @@ extern "C" int spec_lm_head_packed(const void* hidden, const void* Wp, float* lo
     const uint16_t* wp = (const uint16_t*)Wp;
     // More rows than a workgroup holds: the rows are cut into equal groups of at most 160 (a multiple of 16 each), and
     // the grid is groups x panel ranges.  HBM still sees W once; the other groups read it from the L2.
-    const int groups = (M + kPkMaxRows - 1) / kPkMaxRows;
-    const int tm = ((M + groups - 1) / groups + 15) / 16;               // 16-row tiles per group, 1 .. 10
+    int groups = (M + kPkMaxRows - 1) / kPkMaxRows;
+    int tm = ((M + groups - 1) / groups + 15) / 16;                     // 16-row tiles per group, 1 .. 10
     const uint16_t* a = (const uint16_t*)hidden;
     int rc;
+    // Up to 160 rows, groups of at most 80 rows leave registers for 4 panels per wave: a pass is 512 entries wide, which
+    // halves the LDS reads per MFMA and quarters the re-reads of hidden, at the price of W crossing L2 -> CU twice.
+    const bool wide = g_lm_packed_wide == 1 || (g_lm_packed_wide == 0 && false);
+    if (wide && M <= kPkMaxRows && g_lm_packed_waves == 8) {
+        groups = M > kPkMaxRows / 2 ? 2 : 1;
+        tm = ((M + groups - 1) / groups + 15) / 16;                     // 1 .. 5
+        if (tm <= 2) rc = launch_packed<2, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
+        else if (tm <= 4) rc = launch_packed<4, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
+        else rc = launch_packed<5, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
+        if (rc != SPEC_OK) return rc;
+        return check_launch("spec_lm_head_packed");
+    }
     switch (tm) {
         case 1: case 2: rc = launch_packed_auto<2>(a, wp, logits, M, H, V, groups, s); break;
         case 3: case 4: rc = launch_packed_auto<4>(a, wp, logits, M, H, V, groups, s); break;

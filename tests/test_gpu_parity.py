@@ -265,15 +265,18 @@ def test_lm_head_packed_matches_oracle(sv, oracle, M, H, V, std):
     got = logits.cpu().numpy()
     _close(got, ref, f"lm_head_packed {M}x{H}x{V}", sharp=std == 1.0)
     assert np.abs(got - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max()) * math.sqrt(H)
-    # the 4-wave launch variant adds in the same order
+    # the other launch variants (4 waves; passes of 512 entries over row groups of at most 80) add in the same order
     try:
-        sv.spec_set_tuning("lm_packed_waves", 4)
-        again = torch.zeros_like(logits)
-        sv.spec_lm_head_packed(hidden, Wp, again)
-        torch.cuda.synchronize()
-        assert torch.equal(again, logits)
+        for key, value, back in (("lm_packed_waves", 4, 8), ("lm_packed_wide", 1, 0), ("lm_packed_wide", 2, 0)):
+            sv.spec_set_tuning(key, value)
+            again = torch.zeros_like(logits)
+            sv.spec_lm_head_packed(hidden, Wp, again)
+            torch.cuda.synchronize()
+            assert torch.equal(again, logits), key
+            sv.spec_set_tuning(key, back)
     finally:
         sv.spec_set_tuning("lm_packed_waves", 8)
+        sv.spec_set_tuning("lm_packed_wide", 0)
 
 
 def test_lm_head_packed_rejects_bad_shapes(sv):
