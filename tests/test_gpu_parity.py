@@ -752,12 +752,18 @@ def test_tree_acceptance_flags_bad_trees_and_tokens(sv, oracle):
 
 
 # --------------------------------------------------------------------------- whole step
-def _run_step(sv, oracle, cfg, stochastic, fused=False):
+def _run_step(sv, oracle, cfg, stochastic, fused=False, packed=True):
+    """One step as bench.py launches it (packed vocabulary matrix unless `packed` is False or `fused`)."""
     b = wl.make_batch(cfg, device="cuda")
     step = _step(b, cfg)
     qo = b["qo_indptr"].cpu().numpy()
     out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
-    logits = step.lm_head_stats(b["hidden"], b["W"]) if fused else step.lm_head(b["hidden"], b["W"])
+    if fused:
+        logits = step.lm_head_stats(b["hidden"], b["W"])
+    elif packed and cfg.H % 256 == 0:
+        logits = step.lm_head_packed(b["hidden"], step.pack_weights(b["W"]))
+    else:
+        logits = step.lm_head(b["hidden"], b["W"])
     torch.cuda.synchronize()
     ref_attn = _oracle_attn(oracle, b)                   # before the commit changes lengths and pages
     gl = logits.cpu().numpy()
@@ -792,10 +798,11 @@ def _run_step(sv, oracle, cfg, stochastic, fused=False):
     return b, step, out, gl, ref_attn
 
 
-def test_whole_step_tiny_config(sv, oracle):
+@pytest.mark.parametrize("packed", [True, False], ids=["packed", "rowmajor"])
+def test_whole_step_tiny_config(sv, oracle, packed):
     """The smallest workload (4 requests, 5 rows each, short contexts) end to end."""
     cfg = wl.CONFIGS["tiny"]
-    b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=False)
+    b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=False, packed=packed)
     _close(out.float().cpu().numpy(), ref_attn, "tiny attn")
     _close(gl, oracle.lm_head(wl.bf16_bits(b["hidden"]), wl.bf16_bits(b["W"])), "tiny logits")
 
@@ -904,7 +911,10 @@ def test_results_are_bitwise_repeatable_and_stay_inside_their_buffers(sv, oracle
                 af, step.accept_len = guarded((B,), torch.int32, -77)
                 tf, step.out_tokens = guarded((B, b["gamma_max"] + 1), torch.int32, -77)
                 step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
-                step.lm_head(b["hidden"], b["W"])
+                if rep == 1:                         # the packed kernel gives the same bits as the row-major one
+                    step.lm_head_packed(b["hidden"], step.pack_weights(b["W"]))
+                else:
+                    step.lm_head(b["hidden"], b["W"])
                 torch.cuda.synchronize()
                 if rep == 0 and not runs:
                     dp, tokens_s = wl.draft_probs_noisy(cfg, b["qo_indptr"], step.logits)
@@ -953,7 +963,8 @@ def test_step_can_be_captured_in_a_graph_and_replayed(sv, oracle):
     sv.spec_set_tuning("attn_plan", 1)
     try:
         step = _step(b, cfg)
-        logits = step.lm_head(b["hidden"], b["W"])
+        Wp = step.pack_weights(b["W"])
+        logits = step.lm_head_packed(b["hidden"], Wp)
         torch.cuda.synchronize()
         dp, tokens = wl.draft_probs_noisy(cfg, qo, logits)
         tokens = tokens.cuda()
@@ -964,7 +975,7 @@ def test_step_can_be_captured_in_a_graph_and_replayed(sv, oracle):
             for dst, src in zip((pt, sl, fl, fc), pristine):
                 dst.copy_(src)
             step.attn(b["q"], b["k_cache"], b["v_cache"], pt, sl, qo, b["scale"])
-            step.lm_head(b["hidden"], b["W"])
+            step.lm_head_packed(b["hidden"], Wp)
             step.accept(tokens, dp, b["temperature"], b["seeds"], 2, qo)
             step.commit(pt, sl, qo, fl, fc, cfg.P)
 
@@ -1018,6 +1029,9 @@ def test_full_size_configuration(sv, oracle, name):
     b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=stochastic)
     _close(out.float().cpu().numpy(), ref_attn, f"{name} attn")
     _sampled_logits_check(oracle, b, gl)
+    # every logit, against the independent row-major kernels: both add a row's products in the same order
+    packed_logits = step.logits.clone()
+    assert torch.equal(step.lm_head(b["hidden"], b["W"]), packed_logits)
 
 
 def test_full_size_hybrid_mix_properties(sv, oracle):
@@ -1043,7 +1057,7 @@ def test_full_size_hybrid_mix_properties(sv, oracle):
     assert int(step.status.cpu()) == 0
     del ref, out
     # acceptance + commit on the whole batch
-    logits = step.lm_head(b["hidden"], b["W"])
+    logits = step.lm_head_packed(b["hidden"], step.pack_weights(b["W"]))
     torch.cuda.synchronize()
     gl = logits.cpu().numpy()
     _sampled_logits_check(oracle, b, gl, n_cols=64)
