@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="mid", help="workload name in paper_2605_08151_amd.workloads.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-chunk", type=int, default=0, help="override keys per kv split (0 = library heuristic)")
@@ -136,8 +136,10 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     emitted = int(step.stats.cpu()[1])
     assert int(step.status.cpu()) == 0, "a kernel flagged bad input"
-    per_call_ms = {n: float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)]))
-                   for i, n in enumerate(names)}
+    samples = {n: np.array([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)]) for i, n in enumerate(names)}
+    per_call_ms = {n: float(v.mean()) for n, v in samples.items()}
+    per_call_spread = {n: {"median": float(np.median(v)), "p10": float(np.percentile(v, 10)), "p90": float(np.percentile(v, 90))}
+                       for n, v in samples.items()}
 
     # ---- roofline of each call (algorithmic bytes / flops per launch) -----------------------
     kv_tokens = int((b["ctx"] + b["gammas"] + 1).sum())
@@ -183,6 +185,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "per_call_ms": per_call_ms,
+        "per_call_ms_spread": per_call_spread,
         "per_call_roofline": rl,
     }
     print(json.dumps(out))
