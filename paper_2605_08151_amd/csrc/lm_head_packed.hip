@@ -330,13 +330,13 @@ extern "C" int spec_lm_head_packed(const void* hidden, const void* Wp, float* lo
     int tm = ((M + groups - 1) / groups + 15) / 16;                     // 16-row tiles per group, 1 .. 10
     const uint16_t* a = (const uint16_t*)hidden;
     int rc;
-    // Up to 160 rows, groups of at most 80 rows leave registers for 4 panels per wave: a pass is 512 entries wide, which
-    // halves the LDS reads per MFMA and quarters the re-reads of hidden, at the price of W crossing L2 -> CU twice.
-    const bool wide = g_lm_packed_wide == 1 || (g_lm_packed_wide == 0 && false);
-    if (wide && M <= kPkMaxRows && g_lm_packed_waves == 8) {
-        groups = M > kPkMaxRows / 2 ? 2 : 1;
+    // Groups of at most 80 rows leave registers for 4 panels per wave: a pass is 512 entries wide, which halves the LDS
+    // reads per MFMA and quarters the re-reads of hidden, at the price of W crossing L2 -> CU twice as often.
+    if (g_lm_packed_wide == 1 && g_lm_packed_waves == 8) {
+        groups = (M + kPkMaxRows / 2 - 1) / (kPkMaxRows / 2);
         tm = ((M + groups - 1) / groups + 15) / 16;                     // 1 .. 5
-        if (tm <= 2) rc = launch_packed<2, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
+        if (groups > 2) rc = launch_packed<5, 1, 8, false, 4>(a, wp, logits, M, H, V, groups, s);
+        else if (tm <= 2) rc = launch_packed<2, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
         else if (tm <= 4) rc = launch_packed<4, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
         else rc = launch_packed<5, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
         if (rc != SPEC_OK) return rc;
