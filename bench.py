@@ -34,8 +34,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-chunk", type=int, default=0, help="override keys per kv split (0 = library heuristic)")
     ap.add_argument("--fused-stats", action="store_true",
-                    help="spec_lm_head_stats + spec_accept_stats instead of spec_lm_head + spec_accept (same outputs; "
-                         "measured slower per step on MI355X)")
+                    help="the LM head also leaves per-block maxima (spec_lm_head_stats or spec_lm_head_packed_stats) and "
+                         "greedy acceptance reads those instead of the logits (spec_accept_stats); same outputs")
     ap.add_argument("--lm-weights", choices=("auto", "packed", "rowmajor"), default="auto",
                     help="layout of the vocabulary matrix: packed (spec_lm_head_packed; re-laid once before the timed "
                          "region, as at model load) or rowmajor (spec_lm_head); auto = packed whenever the kernel takes "
@@ -72,9 +72,7 @@ def main():
     B, M, V, H = b["B"], b["M"], cfg.V, cfg.H
     step = VerifyStep(B, M, cfg.Hq, cfg.Hkv, cfg.D, H, V, b["gamma_max"], b["max_kv_len"])
     qo = b["qo_indptr"]
-    packed = args.lm_weights == "packed" or (args.lm_weights == "auto" and H % 256 == 0 and not args.fused_stats)
-    if packed and args.fused_stats:
-        sys.exit("bench.py: --fused-stats needs --lm-weights rowmajor")
+    packed = args.lm_weights == "packed" or (args.lm_weights == "auto" and H % 256 == 0)
     Wp = step.pack_weights(b["W"]) if packed else None      # load-time work, not part of a step
     logits = step.lm_head_packed(b["hidden"], Wp) if packed else step.lm_head(b["hidden"], b["W"])
     torch.cuda.synchronize()
@@ -103,14 +101,18 @@ def main():
         if events: events[0].record()
         step.attn(b["q"], kc, vc, pt, sl, qo, b["scale"], want_lse=False)
         if events: events[1].record()
-        if fused:
+        if fused and packed:
+            step.lm_head_packed_stats(b["hidden"], Wp)
+        elif fused:
             step.lm_head_stats(b["hidden"], b["W"])
         elif packed:
             step.lm_head_packed(b["hidden"], Wp)
         else:
             step.lm_head(b["hidden"], b["W"])
         if events: events[2].record()
-        if fused:
+        if fused and packed:
+            step.accept_packed_stats(tokens, draft_probs, b["temperature"], seeds, 0, qo)
+        elif fused:
             step.accept_stats(tokens, draft_probs, b["temperature"], seeds, 0, qo)
         else:
             step.accept(tokens, draft_probs, b["temperature"], seeds, 0, qo)

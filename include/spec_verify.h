@@ -181,6 +181,16 @@ int spec_lm_head_pack(const void* W, void* Wp, int V, int H, void* stream);
 
 int spec_lm_head_packed(const void* hidden, const void* Wp, float* logits, int M, int H, int V, void* stream);
 
+/* spec_lm_head_packed that also leaves the block statistics described at spec_lm_head_stats (same meaning, same
+ * consumer: spec_accept_stats), one block per row for every pass of a workgroup (256 vocabulary entries or fewer).
+ *   blocks = spec_lm_head_packed_stats_blocks(M, H, V) (host): blocks per row; 0 when spec_lm_head_packed does
+ *   not take the shape.  blk_max [M, blocks] fp32, blk_arg [M, blocks] int32 (device, caller-owned, required).
+ * Errors as spec_lm_head_packed. */
+int spec_lm_head_packed_stats_blocks(int M, int H, int V);
+
+int spec_lm_head_packed_stats(const void* hidden, const void* Wp, float* logits, int M, int H, int V,
+                              float* blk_max, int32_t* blk_arg, void* stream);
+
 /* ---------------------------------------------------------------------------
  * spec_accept — accepted length and bonus token per request (Method,
  * "Rollback-Based Mode Selection": after the verification pass the target

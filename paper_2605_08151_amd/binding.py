@@ -22,6 +22,7 @@ EXPORTS = (
     "spec_divergence", "spec_kv_truncate", "spec_compress_prompts",
     "spec_verify_attn_tree", "spec_accept_tree", "spec_kv_commit_tree",
     "spec_lm_head_packed_bytes", "spec_lm_head_pack", "spec_lm_head_packed",
+    "spec_lm_head_packed_stats_blocks", "spec_lm_head_packed_stats",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -67,6 +68,10 @@ def _load():
     lib.spec_lm_head_pack.argtypes = [vp, vp, i32, i32, vp]
     lib.spec_lm_head_packed.restype = i32
     lib.spec_lm_head_packed.argtypes = [vp, vp, vp, i32, i32, i32, vp]
+    lib.spec_lm_head_packed_stats_blocks.restype = i32
+    lib.spec_lm_head_packed_stats_blocks.argtypes = [i32] * 3
+    lib.spec_lm_head_packed_stats.restype = i32
+    lib.spec_lm_head_packed_stats.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
     lib.spec_accept_stats.restype = i32
     lib.spec_accept_stats.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
     lib.spec_verify_attn_tree.restype = i32
@@ -198,6 +203,20 @@ def spec_lm_head_packed(hidden, Wp, logits):
     assert logits.shape[0] == M and Wp.numel() * Wp.element_size() == spec_lm_head_packed_bytes(V, H)
     _check(_lib.spec_lm_head_packed(_ptr(hidden, torch.bfloat16), _ptr(Wp, torch.bfloat16), _ptr(logits, torch.float32),
                                     M, H, V, _stream()))
+
+
+def spec_lm_head_packed_stats_blocks(M, H, V):
+    return int(_lib.spec_lm_head_packed_stats_blocks(int(M), int(H), int(V)))
+
+
+def spec_lm_head_packed_stats(hidden, Wp, logits, blk_max, blk_arg):
+    M, H = hidden.shape
+    V = logits.shape[1]
+    assert logits.shape[0] == M and Wp.numel() * Wp.element_size() == spec_lm_head_packed_bytes(V, H)
+    blocks = spec_lm_head_packed_stats_blocks(M, H, V)
+    assert tuple(blk_max.shape) == (M, blocks) and tuple(blk_arg.shape) == (M, blocks)
+    _check(_lib.spec_lm_head_packed_stats(_ptr(hidden, torch.bfloat16), _ptr(Wp, torch.bfloat16), _ptr(logits, torch.float32),
+                                          M, H, V, _ptr(blk_max, torch.float32), _ptr(blk_arg, torch.int32), _stream()))
 
 
 def spec_accept_workspace_bytes(B, M, V, gamma_max):

@@ -54,12 +54,14 @@ __global__ __launch_bounds__(256) void lm_head_pack_kernel(const uint16_t* __res
 //     next kernel; 263 against 280 us at M = 160); with many groups the L2 absorbs the writes better (1351 against
 //     1504 us at M = 1152).
 // TM: 16-row tiles of hidden (M <= 16 TM); RS: slabs in the W register ring; NW: waves (4 or 8; 16 / NW panels each);
-// NT: nontemporal stores of the logits; TN: panels per wave and pass (2 or 4: a pass is 16 NW TN entries wide).
+// NT: nontemporal stores of the logits; TN: panels per wave and pass (2 or 4: a pass is 16 NW TN entries wide);
+// STATS: also leave per-block maxima for greedy acceptance.
 // ------------------------------------------------------------------------------------------------
-template <int TM, int RS, int NW, bool NT, int TN>
+template <int TM, int RS, int NW, bool NT, int TN, bool STATS>
 __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     const uint16_t* __restrict__ A_all, const uint16_t* __restrict__ Wp, float* __restrict__ C_all,
-    int M_all, int H, int V, int n_panels, int panels_per_wg, bool vec_store, int groups, int rows_per_group)
+    int M_all, int H, int V, int n_panels, int panels_per_wg, bool vec_store, int groups, int rows_per_group,
+    float* __restrict__ blk_max, int32_t* __restrict__ blk_arg, int nblk, int passes_per_range)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int kPassPanels = NW * TN;              // panels per workgroup pass
@@ -82,7 +84,22 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     float* __restrict__ C = C_all + (size_t)group * rows_per_group * V;
     const int p_begin = range * panels_per_wg;
     const int p_end = min(n_panels, p_begin + panels_per_wg);
-    if (p_begin >= p_end) return;
+    // STATS: block b = range * passes_per_range + pass of a row holds the maximum of the logits this workgroup computed
+    // for the row in that pass and its lowest index (NaN / INT_MAX if the block holds a NaN, -inf / INT_MAX for a
+    // block without entries), so that greedy acceptance need not read the logits again.
+    auto fill_empty_blocks = [&](int first_pass) {
+        const int missing = passes_per_range - first_pass;
+        for (int e = tid; e < missing * M; e += kThreads) {
+            const int r = e / missing, q = e - r * missing;
+            const size_t o = (size_t)(group * rows_per_group + r) * nblk + (size_t)range * passes_per_range + first_pass + q;
+            blk_max[o] = -INFINITY;
+            blk_arg[o] = 0x7FFFFFFF;
+        }
+    };
+    if (p_begin >= p_end) {
+        if (STATS) fill_empty_blocks(0);
+        return;
+    }
     const int n_own = p_end - p_begin;
     const int npass = (n_own + kPassPanels - 1) / kPassPanels;
 
@@ -143,12 +160,33 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     unsigned char* buf1 = smem + BM * kPkHPitch;
     constexpr int kPatchPitch = TN * 64 + 16;         // bytes per row of the wave's store patch: 16 rows x 16 TN entries
     unsigned char* patch = smem + 2 * BM * kPkHPitch + wave * (16 * kPatchPitch);
+    // STATS: per row one candidate (value, index) from each wave, merged by the first threads after the next barrier
+    float* cand_v = reinterpret_cast<float*>(smem + 2 * BM * kPkHPitch + NW * 16 * kPatchPitch);   // [BM][NW]
+    int* cand_i = reinterpret_cast<int*>(cand_v + BM * NW);
+    auto merge_candidates = [&](int done_pass) {          // after a barrier that follows the pass's candidate writes
+        for (int r = tid; r < M; r += kThreads) {
+            float best = -INFINITY;
+            int bi = 0x7FFFFFFF;
+            bool nan = false;
+#pragma unroll
+            for (int q = 0; q < NW; ++q) {
+                const float v = cand_v[r * NW + q];
+                const int vi = cand_i[r * NW + q];
+                nan |= (v != v);
+                if (v > best || (v == best && vi < bi)) { best = v; bi = vi; }
+            }
+            const size_t o = (size_t)(group * rows_per_group + r) * nblk + (size_t)range * passes_per_range + done_pass;
+            blk_max[o] = nan ? __builtin_nanf("") : best;
+            blk_arg[o] = nan ? 0x7FFFFFFF : bi;
+        }
+    };
     int pass = 0;
     open_pass(pass);
     open_loads();
     for (;;) {
         stash_h(0, buf0);                             // every wave left the previous pass through a barrier
         __syncthreads();
+        if (STATS && pass > 0) merge_candidates(pass - 1);   // written before this barrier, rewritten 2 * nslab barriers later
         for (int sR = 0; sR < nslab; sR += U) {
 #pragma unroll
             for (int par2 = 0; par2 < U; ++par2) {
@@ -205,6 +243,39 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
             __builtin_amdgcn_sched_barrier(0);
         }
         // acc[tn][tm][i] = C[row 16 tm + l16][entry 16 (st_p0 + tn) + 4 kg + i]
+        if (STATS) {
+            int cslot = l16 * NW + wave;                  // a running slot: ten addresses kept across the pass would spill
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                float best = -INFINITY;
+                int bi = 0x7FFFFFFF;
+                bool nan = false;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int e = (st_p0 + tn) * 16 + kg * 4 + i;
+                        const float v = acc[tn][tm][i];
+                        if (tn < st_np && e < V) {       // ascending e: the first maximum is the lowest index
+                            nan |= (v != v);
+                            if (v > best) { best = v; bi = e; }
+                        }
+                    }
+#pragma unroll
+                for (int sh = 16; sh <= 32; sh <<= 1) {   // the four lanes of a row
+                    const float ov = __shfl_xor(best, sh, 64);
+                    const int oi = __shfl_xor(bi, sh, 64);
+                    nan |= (bool)__shfl_xor((int)nan, sh, 64);
+                    if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+                }
+                if (kg == 0) {
+                    cand_v[cslot] = nan ? __builtin_nanf("") : best;
+                    cand_i[cslot] = bi;
+                }
+                cslot += 16 * NW;
+                asm volatile("" : "+v"(cslot));
+            }
+        }
         if (vec_store) {
             // V % 4 == 0.  The tile is turned through the wave's own LDS patch so that one store instruction writes
             // all the wave's entries of a row (whole cache lines), 4 or 8 rows at a time, instead of 64 bytes of each of 16 rows.
@@ -250,35 +321,54 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
         }
         if (!more) break;
     }
+    if (STATS) {
+        __syncthreads();
+        merge_candidates(npass - 1);
+        fill_empty_blocks(npass);
+    }
 }
 
 int g_lm_packed_wide = 0;      // benchmark hook: 512-entry passes for M <= 160 (0 = automatic, 1 = always, 2 = never)
 int g_lm_packed_waves = 8;     // benchmark hook: waves per workgroup of the packed kernel (4 or 8)
 
-template <int TM, int RS, int NW, bool NT, int TN>
-static int launch_packed(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, int groups, hipStream_t s)
+// panel ranges and panels per range of a launch: ranges is a multiple of 8 (one per XCD and step of the dealing), as many
+// as there are CUs per row group; trailing ranges without panels are dropped 8 at a time
+static void packed_geometry(int V, int groups, int* ranges, int* per_range)
 {
-    constexpr int BM = TM * 16;
-    const size_t smem = 2 * (size_t)BM * kPkHPitch + NW * 16 * (TN * 64 + 16);
-    static size_t granted[kMaxDevices] = {};
-    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_packed_kernel<TM, RS, NW, NT, TN>), smem, granted, "spec_lm_head_packed")) return rc;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         cus = 256;
-    // panel ranges: a multiple of 8 (one per XCD and step of the dealing), as many as there are CUs per row group
     const int n_panels = (V + 15) / 16;
-    int ranges = max(8, cus / groups / 8 * 8);
-    const int per_range = (n_panels + ranges - 1) / ranges;
-    ranges = ((n_panels + per_range - 1) / per_range + 7) / 8 * 8;       // trailing ranges without panels are dropped, 8 at a time
+    const int r0 = max(8, cus / groups / 8 * 8);
+    *per_range = (n_panels + r0 - 1) / r0;
+    *ranges = ((n_panels + *per_range - 1) / *per_range + 7) / 8 * 8;
+}
+
+template <int TM, int RS, int NW, bool NT, int TN, bool STATS = false>
+static int launch_packed(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, int groups, hipStream_t s,
+                         float* blk_max = nullptr, int32_t* blk_arg = nullptr)
+{
+    constexpr int BM = TM * 16;
+    const size_t smem = 2 * (size_t)BM * kPkHPitch + NW * 16 * (TN * 64 + 16) + (STATS ? (size_t)BM * NW * 8 : 0);
+    static size_t granted[kMaxDevices] = {};
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_packed_kernel<TM, RS, NW, NT, TN, STATS>), smem, granted, "spec_lm_head_packed")) return rc;
+    int ranges, per_range;
+    packed_geometry(V, groups, &ranges, &per_range);
+    const int ppr = (per_range + NW * TN - 1) / (NW * TN);
     const bool vec_store = (V % 4 == 0);
-    hipLaunchKernelGGL((lm_head_packed_kernel<TM, RS, NW, NT, TN>), dim3(ranges * groups), dim3(64 * NW), smem, s, a, wp, c, M, H, V, n_panels,
-                       per_range, vec_store, groups, BM);
+    hipLaunchKernelGGL((lm_head_packed_kernel<TM, RS, NW, NT, TN, STATS>), dim3(ranges * groups), dim3(64 * NW), smem, s, a, wp, c, M, H, V,
+                       (V + 15) / 16, per_range, vec_store, groups, BM, blk_max, blk_arg, ranges * ppr, ppr);
     return SPEC_OK;
 }
 
 template <int TM>
-static int launch_packed_auto(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, int groups, hipStream_t s)
+static int launch_packed_auto(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, int groups, hipStream_t s,
+                              float* blk_max, int32_t* blk_arg)
 {
+    if (blk_max) {
+        if (groups > 2) return launch_packed<TM, 1, 8, false, 2, true>(a, wp, c, M, H, V, groups, s, blk_max, blk_arg);
+        return launch_packed<TM, 1, 8, true, 2, true>(a, wp, c, M, H, V, groups, s, blk_max, blk_arg);
+    }
     // measured on MI355X at M = 160, V = 151936 inside the whole verify step: 8 waves 287 us, 4 waves 297 us (a 2-slab
     // W ring is 5 us slower with either); at M = 40 both take 218 us; at M = 576 and 1152 8 waves are 5 % ahead
     if (g_lm_packed_waves == 4) return launch_packed<TM, 1, 4, true, 4>(a, wp, c, M, H, V, groups, s);
@@ -310,29 +400,33 @@ extern "C" int spec_lm_head_pack(const void* W, void* Wp, int V, int H, void* st
     return check_launch("spec_lm_head_pack");
 }
 
-extern "C" int spec_lm_head_packed(const void* hidden, const void* Wp, float* logits, int M, int H, int V, void* stream)
+namespace specv {
+
+static int packed_groups(int M) { return (M + kPkMaxRows - 1) / kPkMaxRows; }
+
+// shared by spec_lm_head_packed (blk_max == nullptr) and spec_lm_head_packed_stats
+static int lm_head_packed_any(const char* who, const void* hidden, const void* Wp, float* logits, int M, int H, int V,
+                              float* blk_max, int32_t* blk_arg, void* stream)
 {
-    using namespace specv;
-    if (M < 0 || H <= 0 || V < 0) return fail(SPEC_EINVAL, "spec_lm_head_packed: negative size (M=%d H=%d V=%d)", M, H, V);
+    if (M < 0 || H <= 0 || V < 0) return fail(SPEC_EINVAL, "%s: negative size (M=%d H=%d V=%d)", who, M, H, V);
     if (M == 0 || V == 0) return SPEC_OK;
-    if (!hidden || !Wp || !logits) return fail(SPEC_EINVAL, "spec_lm_head_packed: NULL pointer argument");
-    if (H % (2 * kPkSlab) != 0)
-        return fail(SPEC_ESHAPE, "spec_lm_head_packed: H=%d must be a multiple of %d", H, 2 * kPkSlab);
+    if (!hidden || !Wp || !logits) return fail(SPEC_EINVAL, "%s: NULL pointer argument", who);
+    if (H % (2 * kPkSlab) != 0) return fail(SPEC_ESHAPE, "%s: H=%d must be a multiple of %d", who, H, 2 * kPkSlab);
     if (!aligned(hidden, 16) || !aligned(Wp, 16) || !aligned(logits, 16))
-        return fail(SPEC_EINVAL, "spec_lm_head_packed: operands must be 16-byte aligned");
+        return fail(SPEC_EINVAL, "%s: operands must be 16-byte aligned", who);
     if ((size_t)V > ((size_t)1 << 32) / (4 * (size_t)(kPkMaxRows + 16)))
-        return fail(SPEC_ESHAPE, "spec_lm_head_packed: V=%d is beyond the 32-bit row offsets of the kernel", V);
+        return fail(SPEC_ESHAPE, "%s: V=%d is beyond the 32-bit row offsets of the kernel", who, V);
     hipStream_t s = (hipStream_t)stream;
     const uint16_t* wp = (const uint16_t*)Wp;
     // More rows than a workgroup holds: the rows are cut into equal groups of at most 160 (a multiple of 16 each), and
     // the grid is groups x panel ranges.  HBM still sees W once; the other groups read it from the L2.
-    int groups = (M + kPkMaxRows - 1) / kPkMaxRows;
+    int groups = packed_groups(M);
     int tm = ((M + groups - 1) / groups + 15) / 16;                     // 16-row tiles per group, 1 .. 10
     const uint16_t* a = (const uint16_t*)hidden;
     int rc;
     // Groups of at most 80 rows leave registers for 4 panels per wave: a pass is 512 entries wide, which halves the LDS
     // reads per MFMA and quarters the re-reads of hidden, at the price of W crossing L2 -> CU twice as often.
-    if (g_lm_packed_wide == 1 && g_lm_packed_waves == 8) {
+    if (!blk_max && g_lm_packed_wide == 1 && g_lm_packed_waves == 8) {
         groups = (M + kPkMaxRows / 2 - 1) / (kPkMaxRows / 2);
         tm = ((M + groups - 1) / groups + 15) / 16;                     // 1 .. 5
         if (groups > 2) rc = launch_packed<5, 1, 8, false, 4>(a, wp, logits, M, H, V, groups, s);
@@ -340,18 +434,42 @@ extern "C" int spec_lm_head_packed(const void* hidden, const void* Wp, float* lo
         else if (tm <= 4) rc = launch_packed<4, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
         else rc = launch_packed<5, 1, 8, true, 4>(a, wp, logits, M, H, V, groups, s);
         if (rc != SPEC_OK) return rc;
-        return check_launch("spec_lm_head_packed");
+        return check_launch(who);
     }
     switch (tm) {
-        case 1: case 2: rc = launch_packed_auto<2>(a, wp, logits, M, H, V, groups, s); break;
-        case 3: case 4: rc = launch_packed_auto<4>(a, wp, logits, M, H, V, groups, s); break;
-        case 5: case 6: rc = launch_packed_auto<6>(a, wp, logits, M, H, V, groups, s); break;
-        case 7: rc = launch_packed_auto<7>(a, wp, logits, M, H, V, groups, s); break;
-        case 8: rc = launch_packed_auto<8>(a, wp, logits, M, H, V, groups, s); break;
-        case 9: rc = launch_packed_auto<9>(a, wp, logits, M, H, V, groups, s); break;
-        default: rc = launch_packed_auto<10>(a, wp, logits, M, H, V, groups, s); break;
+        case 1: case 2: rc = launch_packed_auto<2>(a, wp, logits, M, H, V, groups, s, blk_max, blk_arg); break;
+        case 3: case 4: rc = launch_packed_auto<4>(a, wp, logits, M, H, V, groups, s, blk_max, blk_arg); break;
+        case 5: case 6: rc = launch_packed_auto<6>(a, wp, logits, M, H, V, groups, s, blk_max, blk_arg); break;
+        case 7: rc = launch_packed_auto<7>(a, wp, logits, M, H, V, groups, s, blk_max, blk_arg); break;
+        case 8: rc = launch_packed_auto<8>(a, wp, logits, M, H, V, groups, s, blk_max, blk_arg); break;
+        case 9: rc = launch_packed_auto<9>(a, wp, logits, M, H, V, groups, s, blk_max, blk_arg); break;
+        default: rc = launch_packed_auto<10>(a, wp, logits, M, H, V, groups, s, blk_max, blk_arg); break;
     }
     if (rc != SPEC_OK) return rc;
-    if (int rc2 = check_launch("spec_lm_head_packed")) return rc2;
-    return SPEC_OK;
+    return check_launch(who);
+}
+
+}  // namespace specv
+
+extern "C" int spec_lm_head_packed(const void* hidden, const void* Wp, float* logits, int M, int H, int V, void* stream)
+{
+    return specv::lm_head_packed_any("spec_lm_head_packed", hidden, Wp, logits, M, H, V, nullptr, nullptr, stream);
+}
+
+/* blocks per row of the statistics spec_lm_head_packed_stats writes; 0 = the packed kernel does not take this shape */
+extern "C" int spec_lm_head_packed_stats_blocks(int M, int H, int V)
+{
+    using namespace specv;
+    if (M <= 0 || H <= 0 || V <= 0 || H % (2 * kPkSlab) != 0) return 0;
+    int ranges, per_range;
+    packed_geometry(V, packed_groups(M), &ranges, &per_range);
+    return ranges * ((per_range + 15) / 16);
+}
+
+extern "C" int spec_lm_head_packed_stats(const void* hidden, const void* Wp, float* logits, int M, int H, int V,
+                                         float* blk_max, int32_t* blk_arg, void* stream)
+{
+    using namespace specv;
+    if (M > 0 && V > 0 && (!blk_max || !blk_arg)) return fail(SPEC_EINVAL, "spec_lm_head_packed_stats: NULL pointer argument");
+    return lm_head_packed_any("spec_lm_head_packed_stats", hidden, Wp, logits, M, H, V, blk_max, blk_arg, stream);
 }

@@ -29,6 +29,10 @@ class VerifyStep:
         self.blocks = sv.spec_lm_head_stats_blocks(M, H, V)
         self.blk_max = torch.empty((M, max(1, self.blocks)), dtype=torch.float32, device=dev)
         self.blk_arg = torch.empty((M, max(1, self.blocks)), dtype=torch.int32, device=dev)
+        # the same for the packed LM head (its blocks are the passes of its workgroups)
+        self.pblocks = sv.spec_lm_head_packed_stats_blocks(M, H, V)
+        self.pblk_max = torch.empty((M, max(1, self.pblocks)), dtype=torch.float32, device=dev)
+        self.pblk_arg = torch.empty((M, max(1, self.pblocks)), dtype=torch.int32, device=dev)
 
     def attn(self, q, k_cache, v_cache, page_table, seq_lens, qo_indptr, scale, want_lse=True):
         sv.spec_verify_attn(q, k_cache, v_cache, page_table, seq_lens, qo_indptr, self.attn_out,
@@ -49,6 +53,16 @@ class VerifyStep:
     def lm_head_packed(self, hidden, Wp):
         sv.spec_lm_head_packed(hidden, Wp, self.logits)
         return self.logits
+
+    def lm_head_packed_stats(self, hidden, Wp):
+        sv.spec_lm_head_packed_stats(hidden, Wp, self.logits, self.pblk_max, self.pblk_arg)
+        return self.logits
+
+    def accept_packed_stats(self, tokens, draft_probs, temperature, seeds, round_, qo_indptr):
+        sv.spec_accept_stats(self.logits, tokens, draft_probs, temperature, seeds, round_, qo_indptr, self.accept_len,
+                             self.out_tokens, self.rollback, self.stats, self.gamma_max, self.pblk_max, self.pblk_arg,
+                             self.pblocks, self.status, self.accept_ws)
+        return self.accept_len, self.out_tokens
 
     def lm_head_stats(self, hidden, W):
         sv.spec_lm_head_stats(hidden, W, self.logits, self.blk_max, self.blk_arg)

@@ -758,9 +758,12 @@ def _run_step(sv, oracle, cfg, stochastic, fused=False, packed=True):
     step = _step(b, cfg)
     qo = b["qo_indptr"].cpu().numpy()
     out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
-    if fused:
+    packed = packed and cfg.H % 256 == 0
+    if fused and packed:
+        logits = step.lm_head_packed_stats(b["hidden"], step.pack_weights(b["W"]))
+    elif fused:
         logits = step.lm_head_stats(b["hidden"], b["W"])
-    elif packed and cfg.H % 256 == 0:
+    elif packed:
         logits = step.lm_head_packed(b["hidden"], step.pack_weights(b["W"]))
     else:
         logits = step.lm_head(b["hidden"], b["W"])
@@ -778,7 +781,8 @@ def _run_step(sv, oracle, cfg, stochastic, fused=False, packed=True):
     seeds = b["seeds"]
     if fused:
         # an all-greedy batch may pass no seeds: then no logits are read at all
-        step.accept_stats(tokens.cuda(), dp, b["temperature"], seeds if stochastic else None, 5, b["qo_indptr"])
+        (step.accept_packed_stats if packed else step.accept_stats)(
+            tokens.cuda(), dp, b["temperature"], seeds if stochastic else None, 5, b["qo_indptr"])
     else:
         step.accept(tokens.cuda(), dp, b["temperature"], seeds, 5, b["qo_indptr"])
     torch.cuda.synchronize()
@@ -816,22 +820,32 @@ def test_whole_step_small_hybrid_mix(sv, oracle):
     _close(gl, oracle.lm_head(wl.bf16_bits(b["hidden"]), wl.bf16_bits(b["W"])), "hybrid logits")
 
 
-@pytest.mark.parametrize("M,H,V", [(20, 1024, 32000), (7, 512, 1013), (33, 512, 4097), (160, 512, 20011), (128, 1024, 9000)])
-def test_fused_lm_head_statistics(sv, oracle, M, H, V):
-    """spec_lm_head_stats: same logits as spec_lm_head (bitwise), and block maxima whose merge is each row's
+@pytest.mark.parametrize("layout", ["rowmajor", "packed"])
+@pytest.mark.parametrize("M,H,V", [(20, 1024, 32000), (7, 512, 1013), (33, 512, 4097), (160, 512, 20011), (128, 1024, 9000),
+                                   (300, 256, 5000), (700, 256, 4100)])
+def test_fused_lm_head_statistics(sv, oracle, M, H, V, layout):
+    """The LM head with block statistics writes the same logits as the plain one, and every block holds its range's
     maximum and its lowest index."""
+    if layout == "rowmajor" and M > 160:
+        pytest.skip("the row-major statistics kernel takes at most 160 rows")
     g = torch.Generator(device="cuda").manual_seed(M + V)
     hidden = torch.randn((M, H), generator=g, device="cuda").to(torch.bfloat16)
     W = (torch.randn((V, H), generator=g, device="cuda") / math.sqrt(H)).to(torch.bfloat16)
     W[V // 3] = W[V // 2]                                  # an exact tie between two vocabulary entries
-    blocks = sv.spec_lm_head_stats_blocks(M, H, V)
+    packed = layout == "packed"
+    blocks = (sv.spec_lm_head_packed_stats_blocks if packed else sv.spec_lm_head_stats_blocks)(M, H, V)
     assert blocks > 0
     plain = torch.empty((M, V), dtype=torch.float32, device="cuda")
     fused = torch.full((M, V), 3.0, dtype=torch.float32, device="cuda")
     bm = torch.full((M, blocks), 7.0, dtype=torch.float32, device="cuda")
     ba = torch.full((M, blocks), -5, dtype=torch.int32, device="cuda")
     sv.spec_lm_head(hidden, W, plain)
-    sv.spec_lm_head_stats(hidden, W, fused, bm, ba)
+    if packed:
+        Wp = torch.empty((sv.spec_lm_head_packed_bytes(V, H) // 2,), dtype=torch.bfloat16, device="cuda")
+        sv.spec_lm_head_pack(W, Wp)
+        sv.spec_lm_head_packed_stats(hidden, Wp, fused, bm, ba)
+    else:
+        sv.spec_lm_head_stats(hidden, W, fused, bm, ba)
     torch.cuda.synchronize()
     assert torch.equal(plain, fused)
     gl, bmn, ban = fused.cpu().numpy(), bm.cpu().numpy(), ba.cpu().numpy()
@@ -847,7 +861,8 @@ def test_fused_lm_head_statistics(sv, oracle, M, H, V):
     _close(gl, ref, "fused logits", sharp=True)
 
 
-def test_fused_statistics_carry_nan_rows(sv, oracle):
+@pytest.mark.parametrize("layout", ["rowmajor", "packed"])
+def test_fused_statistics_carry_nan_rows(sv, oracle, layout):
     """A NaN in a hidden row makes that row's logits NaN: flagged through the block statistics exactly as by the scan."""
     cfg = wl.VerifyConfig("nanrow", 31, 6, (2,), ("const", 40), 8, 1, 512, 5003)
     b = wl.make_batch(cfg, device="cuda")
@@ -855,10 +870,18 @@ def test_fused_statistics_carry_nan_rows(sv, oracle):
     results = []
     for fused in (False, True):
         step = _step(b, cfg)
-        logits = step.lm_head_stats(b["hidden"], b["W"]) if fused else step.lm_head(b["hidden"], b["W"])
+        if fused and layout == "packed":
+            logits = step.lm_head_packed_stats(b["hidden"], step.pack_weights(b["W"]))
+            accept = step.accept_packed_stats
+        elif fused:
+            logits = step.lm_head_stats(b["hidden"], b["W"])
+            accept = step.accept_stats
+        else:
+            logits = step.lm_head(b["hidden"], b["W"])
+            accept = step.accept
         torch.cuda.synchronize()
         tokens, _ = wl.draft_tokens_greedy(cfg, b["qo_indptr"], torch.nan_to_num(logits).argmax(1).cpu())
-        (step.accept_stats if fused else step.accept)(tokens.cuda(), None, b["temperature"], None, 0, b["qo_indptr"])
+        accept(tokens.cuda(), None, b["temperature"], None, 0, b["qo_indptr"])
         torch.cuda.synchronize()
         assert int(step.status.cpu()) & sv.FLAG_BAD_LOGITS
         results.append((step.accept_len.cpu().numpy(), step.out_tokens.cpu().numpy(), step.rollback.cpu().numpy(),
@@ -871,15 +894,16 @@ def test_fused_statistics_carry_nan_rows(sv, oracle):
     assert np.array_equal(results[1][0], ref["accept_len"]) and np.array_equal(results[1][1], ref["out_tokens"])
 
 
+@pytest.mark.parametrize("packed", [True, False], ids=["packed", "rowmajor"])
 @pytest.mark.parametrize("name,stochastic", [("tiny", False), ("mid", False), ("hybrid_small", True)])
-def test_whole_step_with_fused_statistics(sv, oracle, name, stochastic):
+def test_whole_step_with_fused_statistics(sv, oracle, name, stochastic, packed):
     """The step through spec_lm_head_stats + spec_accept_stats: same integers as the oracle on the GPU's logits
     (greedy requests decided from block maxima, sampled ones from the scan, in one batch for the mix)."""
     cfg = wl.CONFIGS[name] if name in wl.CONFIGS else wl.VerifyConfig(
         "hybrid_small", 21, 24, (0, 2, 4, 8), ("lognormal", 600, 1.0, 32, 4000), 8, 1, 512, 20000,
         temperature=("alternate", 0.0, 1.0), sigma_qkv=1.0)
-    b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=stochastic, fused=True)
-    assert step.blocks > 0
+    b, step, out, gl, ref_attn = _run_step(sv, oracle, cfg, stochastic=stochastic, fused=True, packed=packed)
+    assert (step.pblocks if packed else step.blocks) > 0
     _close(out.float().cpu().numpy(), ref_attn, f"{name} attn", sharp=name == "hybrid_small")
 
 
