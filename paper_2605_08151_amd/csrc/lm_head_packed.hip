@@ -17,7 +17,7 @@
 namespace specv {
 
 constexpr int kPkSlab = 128;                   // k per hidden slab in LDS
-constexpr int kPkHPitch = kPkSlab * 2 + 16;    // bytes per hidden row in LDS (272: 16 rows -> 16 bank groups)
+constexpr int kPkHPitch = kPkSlab * 2;         // bytes per hidden row in LDS; 16-byte chunk ch of row r sits at position ch ^ (r & 15)
 constexpr int kPkMaxRows = 160;                // rows of hidden per launch
 
 __global__ __launch_bounds__(256) void lm_head_pack_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ Wp,
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
 #pragma unroll
         for (int p = 0; p < H_LOADS; ++p) {
             const int idx = min(tid + p * kThreads, BM * 16 - 1), row = idx >> 4, ch = idx & 15;
-            *reinterpret_cast<u32x4*>(buf + row * kPkHPitch + ch * 16) = hreg[set][p];
+            *reinterpret_cast<u32x4*>(buf + row * kPkHPitch + ((ch ^ (row & 15)) << 4)) = hreg[set][p];
         }
     };
     const int nslab = H / kPkSlab;                    // multiple of U
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
                 // a whole chunk of fragments, which leaves the registers to the W ring.
                 bf16x8 hfq[kHfAhead];
                 auto hfrag = [&](int i) {
-                    return *reinterpret_cast<const bf16x8*>(cur + ((i % TM) * 16 + l16) * kPkHPitch + (i / TM) * 64 + kg * 16);
+                    return *reinterpret_cast<const bf16x8*>(cur + ((i % TM) * 16 + l16) * kPkHPitch + ((((i / TM) * 4 + kg) ^ l16) << 4));
                 };
 #pragma unroll
                 for (int i = 0; i < kHfAhead; ++i) hfq[i] = hfrag(i);
