@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void lm_head_tiled_kernel(
 //   * C^T tiles come out with 4 consecutive vocabulary entries per lane: 16-byte stores along V.
 // ------------------------------------------------------------------------------------------------
 constexpr int kSlab = 128;                   // k per hidden slab in LDS
-constexpr int kHPitch = kSlab * 2 + 16;      // bytes per hidden row in LDS (272: 16 rows -> 16 bank groups)
+constexpr int kHPitch = kSlab * 2;           // bytes per hidden row in LDS; 16-byte chunk ch of row r sits at position ch ^ (r & 15)
 constexpr int kPassCols = 128;               // vocabulary entries per workgroup pass (4 wave columns x 32)
 
 // TM: 16-row tiles of hidden in total; MS: wave rows (the 4*MS waves form a 4 x MS grid: wave column = 32
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
 #pragma unroll
         for (int p = 0; p < H_LOADS; ++p) {
             const int idx = min(tid + p * kThreads, BM * 16 - 1), row = idx >> 4, ch = idx & 15;
-            *reinterpret_cast<u32x4*>(buf + row * kHPitch + ch * 16) = hreg[set][p];
+            *reinterpret_cast<u32x4*>(buf + row * kHPitch + ((ch ^ (row & 15)) << 4)) = hreg[set][p];
         }
     };
     // First requests of a pass, in the order of the steady state (hidden slab, then W chunks), so that the
@@ -236,13 +236,13 @@ __global__ __launch_bounds__(256 * MS, 1) void lm_head_skinny_kernel(
                 bf16x8 hf[2][TMH];
 #pragma unroll
                 for (int tm = 0; tm < TMH; ++tm)
-                    hf[0][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + kg * 16);
+                    hf[0][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + ((kg ^ l16) << 4));
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     if (c < 3) {
 #pragma unroll
                         for (int tm = 0; tm < TMH; ++tm)
-                            hf[(c + 1) & 1][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + (c + 1) * 64 + kg * 16);
+                            hf[(c + 1) & 1][tm] = *reinterpret_cast<const bf16x8*>(cur + (hrow0 + tm * 16) * kHPitch + ((((c + 1) * 4 + kg) ^ l16) << 4));
                     }
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn) {
