@@ -68,7 +68,8 @@ int spec_version(void);
 /* Benchmark hook (host, process-wide): overrides a launch heuristic; never changes results beyond fp32
  * summation order.  Keys: "attn_chunk" = keys per kv split of spec_verify_attn, 0 = automatic;
  * "attn_plan" = device-built balanced work list of spec_verify_attn, 0 = automatic, 1 = always (B <= 1024),
- * 2 = never; "attn_plan_waves" = work items per CU that list aims at, 0 = automatic;
+ * 2 = never; "attn_plan_waves" = work items per CU that list aims at, 0 = automatic; "attn_nr3_waves" = waves per
+ * workgroup of spec_verify_attn when a request has 33..48 query rows per kv head, 8 (default) or 4;
  * "lm_kernel" = kernel used by spec_lm_head, 0 = automatic (weight-streaming kernel for M <= 160, MFMA-bound
  * kernel above), 1 = weight-streaming, 2 = MFMA-bound with direct global->LDS loads, 3 = plain tiled,
  * 4..7 = weight-streaming variants (wave count / register-ring depth), 8 = MFMA-bound with register staging;

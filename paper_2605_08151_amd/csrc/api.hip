@@ -17,6 +17,7 @@ extern int g_lm_kernel;
 extern int g_lm_kernel_waves;
 extern int g_attn_plan;
 extern int g_attn_plan_waves;
+extern int g_attn_nr3_waves;
 extern int g_lm_packed_waves;
 extern int g_lm_packed_wide;
 
@@ -40,6 +41,7 @@ extern "C" int spec_set_tuning(const char* key, int value)
     if (key && std::strcmp(key, "lm_big_waves") == 0) { specv::g_lm_kernel_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_plan") == 0) { specv::g_attn_plan = value; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_plan_waves") == 0) { specv::g_attn_plan_waves = value; return SPEC_OK; }
+    if (key && std::strcmp(key, "attn_nr3_waves") == 0) { specv::g_attn_nr3_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_packed_wide") == 0) { specv::g_lm_packed_wide = value; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_packed_waves") == 0) { specv::g_lm_packed_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     return specv::fail(SPEC_EINVAL, "spec_set_tuning: unknown key '%s'", key ? key : "(null)");

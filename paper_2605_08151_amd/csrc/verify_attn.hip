@@ -655,7 +655,8 @@ static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
     return (int)((target + step_keys - 1) / step_keys * step_keys);
 }
 
-static int attn_waves(int NR) { return NR <= 2 ? 8 : 4; }      // 8 waves need <= 256 registers per lane
+int g_attn_nr3_waves = 8;  // benchmark hook: waves per workgroup when a request has 3 row tiles (8, or 4 with two K/V buffers each)
+static int attn_waves(int NR) { return NR <= 2 || (NR == 3 && g_attn_nr3_waves == 8) ? 8 : 4; }      // 8 waves need <= 256 registers per lane
 
 // Balanced work list (verify_attn_plan_kernel): used when requests are long enough for a few microseconds of
 // planning to pay, numerous enough for their length spread to matter, and the fixed chunk would split them anyway.
@@ -717,10 +718,15 @@ static int launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t s)
 template <int NR>
 static int launch_attn(const AttnParams& p, dim3 grid, hipStream_t s)
 {
-    // up to 32 query rows: 8 waves (two per SIMD hide each other's loads, one K/V buffer per wave);
+    // up to 48 query rows: 8 waves (two per SIMD hide each other's loads, one K/V buffer per wave; with 3 row tiles
+    // 238 registers, and 3-4 % faster than 4 waves on 32-64k contexts);
     // more rows need > 256 registers per lane: 4 waves, each double-buffering its own pages
-    constexpr int NW = NR <= 2 ? 8 : 4;
-    constexpr int NBUF = (NR <= 2 || NR >= 7) ? 1 : 2;   // 7-8 row tiles leave no LDS for a second buffer
+    if constexpr (NR == 3) {
+        if (g_attn_nr3_waves != 8)
+            return p.splits == 1 ? launch_attn_one<NR, 4, 2, true>(p, grid, s) : launch_attn_one<NR, 4, 2, false>(p, grid, s);
+    }
+    constexpr int NW = NR <= 3 ? 8 : 4;
+    constexpr int NBUF = (NR <= 3 || NR >= 7) ? 1 : 2;   // 7-8 row tiles leave no LDS for a second buffer
     return p.splits == 1 ? launch_attn_one<NR, NW, NBUF, true>(p, grid, s) : launch_attn_one<NR, NW, NBUF, false>(p, grid, s);
 }
 
