@@ -18,7 +18,7 @@ namespace specv {
 
 constexpr int kPkSlab = 128;                   // k per hidden slab in LDS
 constexpr int kPkHPitch = kPkSlab * 2;         // bytes per hidden row in LDS; 16-byte chunk ch of row r sits at position ch ^ (r & 15)
-constexpr int kPkMaxRows = 160;                // rows of hidden per launch
+constexpr int kPkMaxRows = 160;                // rows of hidden per row group (one workgroup's share)
 
 __global__ __launch_bounds__(256) void lm_head_pack_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ Wp,
                                                            int V, int H, size_t n_chunks)
@@ -39,9 +39,10 @@ __global__ __launch_bounds__(256) void lm_head_pack_kernel(const uint16_t* __res
 
 // ------------------------------------------------------------------------------------------------
 // One persistent workgroup of NW waves per CU owns a contiguous range of panels and walks it in passes of at most
-// 16 panels, cut so that all passes of a workgroup are equally wide (whatever V is, every CU streams at the same
-// rate to the end).  Inside a pass wave w takes up to 16 / NW consecutive panels and all rows of hidden; with
-// NW = 8 two waves share each SIMD and one's MFMAs cover the other's waits (10 us of 297 at M = 160):
+// NW * TN panels (16 = 256 vocabulary entries by default), cut so that all passes of a workgroup are equally wide
+// (whatever V is, every CU streams at the same rate to the end).  Inside a pass wave w takes up to TN consecutive
+// panels and all rows of hidden; with NW = 8 two waves share each SIMD and one's MFMAs cover the other's waits
+// (10 us of 297 at M = 160):
 //   * W goes from HBM straight into registers in operand order through a ring of RS slabs of 128 k, refilled
 //     right after the MFMAs that consumed a chunk pair; no W byte touches LDS.
 //   * hidden is staged through LDS in 128-k slabs shared by the waves, requested two slabs ahead: loads retire
@@ -53,8 +54,9 @@ __global__ __launch_bounds__(256) void lm_head_pack_kernel(const uint16_t* __res
 //     row, 128 or 256 bytes).  With one or two row groups they are stored nontemporal (nobody reads them before the
 //     next kernel; 263 against 280 us at M = 160); with many groups the L2 absorbs the writes better (1351 against
 //     1504 us at M = 1152).
-// TM: 16-row tiles of hidden (M <= 16 TM); RS: slabs in the W register ring; NW: waves (4 or 8; 16 / NW panels each);
-// NT: nontemporal stores of the logits; TN: panels per wave and pass (2 or 4: a pass is 16 NW TN entries wide);
+// TM: 16-row tiles of hidden per row group (rows <= 16 TM); RS: slabs in the W register ring (1 in every launch: 2
+// measured 5 us slower at M = 160 and equal above); NW: waves (4 or 8); NT: nontemporal stores of the logits;
+// TN: panels per wave and pass (2 or 4: a pass is 16 NW TN entries wide);
 // STATS: also leave per-block maxima for greedy acceptance.
 // ------------------------------------------------------------------------------------------------
 template <int TM, int RS, int NW, bool NT, int TN, bool STATS>
