@@ -155,6 +155,21 @@ def main():
     per_call_spread = {n: {"median": float(np.median(v)), "p10": float(np.percentile(v, 10)), "p90": float(np.percentile(v, 90))}
                        for n, v in samples.items()}
 
+    # The same LM head on the row-major matrix (spec_lm_head), outside the timed region, for comparison with the packed call
+    rowmajor_lm_ms = None
+    if packed:
+        e = [new_event() for _ in range(21)]
+        for i in range(5):
+            step.lm_head(b["hidden"], b["W"])
+        e[0].record()
+        for i in range(20):
+            step.lm_head(b["hidden"], b["W"])
+            e[i + 1].record()
+        torch.cuda.synchronize()
+        rowmajor_lm_ms = float(np.mean([e[i].elapsed_time(e[i + 1]) for i in range(20)]))
+        step.lm_head_packed(b["hidden"], Wp)              # leave the logits as the step left them
+        torch.cuda.synchronize()
+
     # ---- roofline of each call (algorithmic bytes / flops per launch) -----------------------
     kv_tokens = int((b["ctx"] + b["gammas"] + 1).sum())
     attn_bytes = kv_tokens * cfg.Hkv * cfg.D * 2 * 2 + 2 * M * cfg.Hq * cfg.D * 2
@@ -194,6 +209,7 @@ def main():
                                f"Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} page={cfg.P} H={H} V={V} "
                                f"temperature={cfg.temperature} seed={cfg.seed}",
                    "lm_weights": "packed" if packed else "rowmajor",
+                   "lm_head_ms_on_rowmajor_weights_back_to_back": rowmajor_lm_ms,
                    "emitted_tokens_per_step": emitted, "scored_positions_per_step": M,
                    "scored_positions_per_s": M / (ms_per_step * 1e-3), "kv_tokens": kv_tokens},
         "roofline": roofline,
