@@ -457,7 +457,15 @@ def test_kv_commit_is_bit_exact(sv, oracle):
 def test_empty_batch_calls_are_noops(sv):
     z32 = torch.zeros(1, dtype=torch.int32, device="cuda")
     sv.spec_kv_commit(z32.view(1, 1), z32[:0], z32, z32[:0], z32, z32.clone(), 16, None)
+    # no rows: the LM heads launch nothing and leave the (empty) logits alone; no entries: nothing to pack
+    W = torch.ones((48, 256), dtype=torch.bfloat16, device="cuda")
+    Wp = torch.full((sv.spec_lm_head_packed_bytes(48, 256) // 2,), 5.0, dtype=torch.bfloat16, device="cuda")
+    none = torch.zeros((0, 256), dtype=torch.bfloat16, device="cuda")
+    sv.spec_lm_head(none, W, torch.zeros((0, 48), dtype=torch.float32, device="cuda"))
+    sv.spec_lm_head_packed(none, Wp, torch.zeros((0, 48), dtype=torch.float32, device="cuda"))
+    sv.spec_lm_head_pack(W[:0], Wp[:0])
     torch.cuda.synchronize()
+    assert (Wp == 5.0).all()
 
 
 # --------------------------------------------------------------------------- candidates of the next round
