@@ -155,20 +155,33 @@ def main():
     per_call_spread = {n: {"median": float(np.median(v)), "p10": float(np.percentile(v, 10)), "p90": float(np.percentile(v, 90))}
                        for n, v in samples.items()}
 
-    # The same LM head on the row-major matrix (spec_lm_head), outside the timed region, for comparison with the packed call
+    del ev, ev_warm, settled                              # hundreds of live events slow later launches down now and then
+
+    # Calls back to back (20 launches between two events, outside the timed region)
+    def back_to_back(fn, n=20):
+        for i in range(3):
+            fn(i)
+        e0, e1 = new_event(), new_event()
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+    # the same LM head on the row-major matrix (spec_lm_head), for comparison with the packed call
     rowmajor_lm_ms = None
     if packed:
-        e = [new_event() for _ in range(21)]
-        for i in range(5):
-            step.lm_head(b["hidden"], b["W"])
-        e[0].record()
-        for i in range(20):
-            step.lm_head(b["hidden"], b["W"])
-            e[i + 1].record()
-        torch.cuda.synchronize()
-        rowmajor_lm_ms = float(np.mean([e[i].elapsed_time(e[i + 1]) for i in range(20)]))
+        rowmajor_lm_ms = back_to_back(lambda i: step.lm_head(b["hidden"], b["W"]))
         step.lm_head_packed(b["hidden"], Wp)              # leave the logits as the step left them
         torch.cuda.synchronize()
+    # attention (K/V pools rotating) and acceptance: their in-step figures above carry the events' own few microseconds,
+    # which is several per cent of these two calls
+    pt0, sl0 = b["page_table"], b["seq_lens"]            # the pristine table: no commit runs here
+    b2b_ms = {
+        "verify_attn": back_to_back(lambda i: step.attn(b["q"], b["k_caches"][i % kv_copies], b["v_caches"][i % kv_copies],
+                                                        pt0, sl0, qo, b["scale"], want_lse=False)),
+        "accept": back_to_back(lambda i: step.accept(tokens, draft_probs, b["temperature"], seeds, 0, qo)),
+    }
 
     # ---- roofline of each call (algorithmic bytes / flops per launch) -----------------------
     kv_tokens = int((b["ctx"] + b["gammas"] + 1).sum())
@@ -185,6 +198,9 @@ def main():
     }
     for r in rl.values():
         r["frac"] = r["achieved"] / r["peak"]
+    for n, nbytes in (("verify_attn", attn_bytes), ("accept", accept_bytes)):
+        rl[n]["back_to_back_ms"] = b2b_ms[n]
+        rl[n]["back_to_back_frac"] = nbytes / b2b_ms[n] / 1e6 / HBM_PEAK_GBS
     dominant = names[dom]
     # the LM head is priced against the roof that binds it at this M: weight streaming (HBM) when the
     # arithmetic intensity is under the ridge, MFMA otherwise
