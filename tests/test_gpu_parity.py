@@ -537,6 +537,90 @@ def test_next_round_follows_acceptance_on_the_device(sv, oracle):
     assert mode[0] == oracle.next_mode(int(r["stats"][0]), int(r["stats"][1]), len(gammas), 5, 1.0, 10.0)[0]
 
 
+def test_four_rounds_chained_on_the_device(sv, oracle):
+    """Verify -> accept -> commit -> next round's candidates, four rounds in a row with the state (lengths, page table,
+    free list, candidates) carried from call to call on the device; the oracle runs the same loop.  Only the page
+    allocation for the new candidate rows is done on the host (the library frees pages, it does not hand them out)."""
+    from paper_2605_08151_amd.step import VerifyStep
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, D, P, H, V, gmax = 6, 8, 1, 128, 16, 256, 997, 4
+    num_pages, max_pages = 96, 12
+    g = torch.Generator(device="cuda").manual_seed(3)
+    kc = torch.randn((num_pages, Hkv, P, D), generator=g, device="cuda").to(torch.bfloat16)   # every page holds "some" K/V
+    vc = torch.randn((num_pages, Hkv, P, D), generator=g, device="cuda").to(torch.bfloat16)
+    W = (torch.randn((V, H), generator=g, device="cuda") / math.sqrt(H)).to(torch.bfloat16)
+    Wp = torch.empty((sv.spec_lm_head_packed_bytes(V, H) // 2,), dtype=torch.bfloat16, device="cuda")
+    sv.spec_lm_head_pack(W, Wp)
+    # host mirror of the state; the device copies are compared with it after every call that changes them
+    seq = rng.integers(20, 100, B).astype(np.int32)
+    pt = np.full((B, max_pages), -1, np.int32)
+    perm = rng.permutation(num_pages).astype(np.int32)
+    used = 0
+    for i in range(B):
+        n = (seq[i] + P - 1) // P
+        pt[i, :n] = perm[used:used + n]
+        used += n
+    fl = np.full(num_pages, -1, np.int32)
+    fc = np.array([num_pages - used], np.int32)
+    fl[:fc[0]] = perm[used:]
+    gam = rng.integers(0, gmax + 1, B)
+    qo = np.zeros(B + 1, np.int32)
+    qo[1:] = np.cumsum(gam + 1)
+    tokens = rng.integers(0, V, qo[-1]).astype(np.int32)
+    temp = np.array([0.0, 0.8] * (B // 2), np.float32)
+    seeds = rng.integers(0, 2 ** 62, B).astype(np.uint64)
+    d_pt, d_seq = torch.from_numpy(pt).cuda(), torch.from_numpy(seq).cuda()
+    d_fl, d_fc = torch.from_numpy(fl).cuda(), torch.from_numpy(fc).cuda()
+    d_temp, d_seeds = torch.from_numpy(temp).cuda(), torch.from_numpy(seeds.view(np.int64)).cuda()
+    modes = []
+    for rnd in range(4):
+        M = int(qo[-1])
+        # pages for the candidate rows (positions c_i .. c_i + gamma_i): taken from the top of the free list, on both sides
+        for i in range(B):
+            for pg in range((seq[i] + P - 1) // P, (seq[i] + gam[i] + 1 + P - 1) // P):
+                fc[0] -= 1
+                pt[i, pg] = fl[fc[0]]
+                fl[fc[0]] = -1
+        d_pt.copy_(torch.from_numpy(pt)); d_fl.copy_(torch.from_numpy(fl)); d_fc.copy_(torch.from_numpy(fc))
+        d_qo, d_tok = torch.from_numpy(qo).cuda(), torch.from_numpy(tokens).cuda()
+        q = torch.randn((M, Hq, D), generator=g, device="cuda").to(torch.bfloat16)
+        hidden = torch.randn((M, H), generator=g, device="cuda").to(torch.bfloat16)
+        step = VerifyStep(B, M, Hq, Hkv, D, H, V, gmax, int((seq + gam + 1).max()))
+        scale = 1.0 / math.sqrt(D)
+        out = step.attn(q, kc, vc, d_pt, d_seq, d_qo, scale)
+        logits = step.lm_head_packed(hidden, Wp)
+        step.accept(d_tok, None, d_temp, d_seeds, rnd, d_qo)
+        torch.cuda.synchronize()
+        _close(out.float().cpu().numpy(), oracle.verify_attn(wl.bf16_bits(q), wl.bf16_bits(kc), wl.bf16_bits(vc), pt, seq, qo, scale),
+               f"round {rnd} attention", sharp=True)
+        gl = logits.cpu().numpy()
+        _close(gl, oracle.lm_head(wl.bf16_bits(hidden), wl.bf16_bits(W)), f"round {rnd} logits", sharp=True)
+        ref = oracle.accept(gl, tokens, None, temp, seeds, rnd, qo, gmax)
+        assert np.array_equal(step.accept_len.cpu().numpy(), ref["accept_len"]), rnd
+        assert np.array_equal(step.out_tokens.cpu().numpy(), ref["out_tokens"]), rnd
+        step.commit(d_pt, d_seq, d_qo, d_fl, d_fc, P)
+        oracle.kv_commit(pt, seq, qo, ref["accept_len"], fl, fc, P)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_pt.cpu().numpy(), pt) and np.array_equal(d_seq.cpu().numpy(), seq), rnd
+        assert int(d_fc.cpu()) == int(fc[0]) and np.array_equal(d_fl.cpu().numpy()[:fc[0]], fl[:fc[0]]), rnd
+        assert int(step.status.cpu()) == 0
+        # the drafter's continuation: right about the bonus for two requests in three
+        bonus = ref["out_tokens"][np.arange(B), ref["accept_len"]]
+        cont = rng.integers(0, V, (B, gmax + 1)).astype(np.int32)
+        right = rng.random(B) < 0.67
+        cont[right, 0] = bonus[right]
+        cl = np.full(B, gmax + 1, np.int32)
+        mode, _, _ = sv.spec_next_mode(step.stats.cpu().numpy(), gmax + 1, 1.0, 12.0)
+        assert mode == oracle.next_mode(int(ref["rollback"].sum()), int((ref["accept_len"] + 1).sum()), B, gmax + 1, 1.0, 12.0)[0]
+        modes.append(mode)
+        nxt = _assemble_both(sv, oracle, step.accept_len.cpu().numpy(), step.out_tokens.cpu().numpy(), qo, cont, cl, None, None,
+                             mode, gmax)
+        qo, tokens = nxt["qo_indptr"].copy(), nxt["tokens"].copy()
+        gam = np.diff(qo) - 1
+        fl[fc[0]:] = -1                                   # entries above the count are unspecified on the device
+    assert (seq >= 24).all() and len(modes) == 4
+
+
 def test_next_round_host_rejections(sv):
     z = torch.zeros(8, dtype=torch.int32, device="cuda")
     with pytest.raises(sv.SpecError):                  # unknown mode
