@@ -42,6 +42,24 @@ def test_host_side_argument_checks_need_no_gpu():
     lib.spec_accept_workspace_bytes.restype = ctypes.c_size_t
     lib.spec_accept_workspace_bytes.argtypes = [ctypes.c_int] * 4
     assert lib.spec_accept_workspace_bytes(32, 160, 151936, 4) > 0
+    # the packed LM head: size arithmetic, and shapes and pointers rejected before anything is launched
+    lib.spec_lm_head_packed_bytes.restype = ctypes.c_size_t
+    lib.spec_lm_head_packed_bytes.argtypes = [ctypes.c_int] * 2
+    assert lib.spec_lm_head_packed_bytes(151936, 4096) == 151936 * 4096 * 2
+    assert lib.spec_lm_head_packed_bytes(1013, 256) == 1024 * 256 * 2          # entries padded to whole panels of 16
+    assert lib.spec_lm_head_packed_bytes(0, 256) == 0
+    lib.spec_lm_head_packed.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 3 + [ctypes.c_void_p]
+    assert lib.spec_lm_head_packed(None, None, None, 4, 256, 40, None) == -1    # NULL operands
+    assert lib.spec_lm_head_packed(None, None, None, 0, 256, 40, None) == 0     # no rows: nothing to do
+    assert lib.spec_lm_head_packed(None, None, None, -1, 256, 40, None) == -1
+    one = ctypes.c_void_p(256)                                                  # aligned, never dereferenced on the host
+    assert lib.spec_lm_head_packed(one, one, one, 4, 192, 40, None) == -2       # H must be a multiple of 256
+    assert b"256" in lib.spec_last_error_string()
+    lib.spec_lm_head_pack.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int] * 2 + [ctypes.c_void_p]
+    assert lib.spec_lm_head_pack(one, one, 40, 48, None) == -2                  # H must be a multiple of 32
+    assert lib.spec_lm_head_pack(None, None, 0, 64, None) == 0
+    lib.spec_lm_head_packed_stats_blocks.argtypes = [ctypes.c_int] * 3
+    assert lib.spec_lm_head_packed_stats_blocks(160, 192, 4000) == 0
 
 
 def test_binding_names_match_the_header():
