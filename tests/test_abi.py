@@ -55,6 +55,7 @@ def test_host_side_argument_checks_need_no_gpu():
     one = ctypes.c_void_p(256)                                                  # aligned, never dereferenced on the host
     assert lib.spec_lm_head_packed(one, one, one, 4, 192, 40, None) == -2       # H must be a multiple of 256
     assert b"256" in lib.spec_last_error_string()
+    assert lib.spec_lm_head_packed(one, one, one, 4, 256, 7_000_000, None) == -2    # row offsets would leave 32 bits
     lib.spec_lm_head_pack.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int] * 2 + [ctypes.c_void_p]
     assert lib.spec_lm_head_pack(one, one, 40, 48, None) == -2                  # H must be a multiple of 32
     assert lib.spec_lm_head_pack(None, None, 0, 64, None) == 0
