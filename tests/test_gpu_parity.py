@@ -250,7 +250,8 @@ def test_lm_head_pack_is_the_documented_permutation(sv, V, H):
 
 @pytest.mark.parametrize("M,H,V,std", [(20, 1024, 32000, 0.02), (7, 256, 1013, 1.0), (160, 512, 4100, 1.0), (45, 768, 3001, 1.0),
                                        (300, 256, 777, 1.0), (1, 256, 5, 1.0), (64, 256, 128, 1.0), (97, 512, 70001, 1.0),
-                                       (130, 256, 16 * 256 * 16 + 4, 1.0), (161, 256, 2049, 1.0), (576, 512, 9000, 1.0), (1153, 256, 4104, 1.0)])
+                                       (130, 256, 16 * 256 * 16 + 4, 1.0), (161, 256, 2049, 1.0), (576, 512, 9000, 1.0), (1153, 256, 4104, 1.0),
+                                       (3, 256, 1000004, 1.0)])                  # a million entries: 16 passes per workgroup
 def test_lm_head_packed_matches_oracle(sv, oracle, M, H, V, std):
     g = torch.Generator(device="cuda").manual_seed(M * 7 + V)
     hs, ws = (1.0, 1.0 / math.sqrt(H)) if std == 1.0 else (std, std)
