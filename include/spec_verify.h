@@ -65,16 +65,25 @@ const char* spec_last_error_string(void);
 /* Library version, major * 1000 + minor. host. */
 int spec_version(void);
 
-/* Benchmark hook (host, process-wide): overrides a launch heuristic; never changes results beyond fp32
- * summation order.  Keys: "attn_chunk" = keys per kv split of spec_verify_attn, 0 = automatic;
- * "attn_plan" = device-built balanced work list of spec_verify_attn, 0 = automatic, 1 = always (B <= 1024),
- * 2 = never; "attn_plan_waves" = work items per CU that list aims at, 0 = automatic; "attn_nr3_waves" = waves per
- * workgroup of spec_verify_attn when a request has 33..48 query rows per kv head, 8 (default) or 4;
- * "lm_kernel" = kernel used by spec_lm_head, 0 = automatic (weight-streaming kernel for M <= 160, MFMA-bound
- * kernel above), 1 = weight-streaming, 2 = MFMA-bound with direct global->LDS loads, 3 = plain tiled,
- * 4..7 = weight-streaming variants (wave count / register-ring depth), 8 = MFMA-bound with register staging;
- * "lm_big_waves" = waves per workgroup of the MFMA-bound kernels, 4 or 8 (default);
- * "lm_packed_waves" = waves per workgroup of spec_lm_head_packed, 4 or 8 (default).
+/* Benchmark hook (host).  Overrides a launch heuristic; never changes results beyond fp32 summation order.
+ * The settings are PROCESS-WIDE (one value per key for all threads and devices).  Each is a single word that is
+ * written and read atomically, so a call racing with a launch on another thread is safe, but which of the two
+ * values that launch sees is unspecified: set the keys before the serving threads start, as a benchmark does.
+ * The verification calls themselves keep no other mutable state.  Keys:
+ *   "attn_chunk"       keys per kv split of spec_verify_attn; 0 = automatic.
+ *   "attn_plan"        device-built balanced work list of spec_verify_attn: 0 = automatic, 1 = always
+ *                      (B <= 1024), 2 = never.
+ *   "attn_plan_waves"  work items per CU that list aims at; 0 = automatic.
+ *   "attn_nr3_waves"   waves per workgroup of spec_verify_attn when a request has 33..48 query rows per kv
+ *                      head: 8 (default) or 4.
+ *   "lm_kernel"        kernel used by spec_lm_head: 0 = automatic (weight-streaming kernel for M <= 160,
+ *                      MFMA-bound kernel above), 1 = weight-streaming, 2 = MFMA-bound with direct global->LDS
+ *                      loads, 3 = plain tiled, 4..7 = weight-streaming variants (wave count / register-ring
+ *                      depth), 8 = MFMA-bound with register staging.
+ *   "lm_big_waves"     waves per workgroup of the MFMA-bound kernels of spec_lm_head: 4 or 8 (default).
+ *   "lm_packed_waves"  waves per workgroup of the weight-streaming kernel of spec_lm_head_packed: 4 or 8 (default).
+ *   "lm_packed_wide"   that kernel with passes of 512 vocabulary entries over row groups of at most 80 rows:
+ *                      0 = automatic (off), 1 = always, 2 = never.
  * A forced kernel that cannot take the shape falls back to the plain tiled one.  Unknown key: SPEC_EINVAL. */
 int spec_set_tuning(const char* key, int value);
 
@@ -295,9 +304,9 @@ int spec_kv_commit(int32_t* page_table, int max_pages_per_seq, int32_t* seq_lens
  *     meanwhile starts with b (cont_len[i] >= 1 and cont[i][0] == b; the
  *     reading taken for Consistent()).  Candidate [b, cont[i][1 .. 1+g)],
  *     g = min(cont_len[i] - 1, gamma_next).
- *   otherwise the request is in the rollback set ("its speculative prefix is
- *     rejected ... or its previously prepared draft continuation is
- *     invalidated", Method, "Rollback-Based Mode Selection"):
+ *   otherwise the request is in the rollback set (Method, "Rollback-Based Mode Selection": a request
+ *     belongs to it when the verified drafts were not all accepted, or when the continuation the drafter
+ *     prepared in the meantime no longer fits what verification produced):
  *     mode SPEC_MODE_ORDINARY with repair != NULL: [b, repair[i][0 .. g)],
  *       g = min(repair_len[i], gamma_next) (the continuation regenerated from b);
  *     mode SPEC_MODE_PARALLEL: [b] (the padded candidate, ragged: gamma = 0).

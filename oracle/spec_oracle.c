@@ -392,8 +392,9 @@ int oracle_next_mode(int rollback_count, int emitted, int B, double gamma, doubl
  * A request is stable iff all its drafts were accepted and the prepared
  * continuation agrees with what the target committed, i.e. cont_len >= 1 and
  * cont[0] == b (the reading taken for Consistent()); otherwise it is in the
- * rollback set: "its speculative prefix is rejected ... or its previously
- * prepared draft continuation is invalidated by the verification result".
+ * rollback set (Method, "Rollback-Based Mode Selection": membership means that
+ * some verified draft was not accepted, or that the continuation prepared in the
+ * meantime no longer fits what verification produced).
  *   stable:              y = [b, cont[1 .. 1+g)]           g = min(cont_len-1, gamma_next)
  *   rollback, ORDINARY:  y = [b, repair[0 .. g)]           g = min(repair_len, gamma_next)
  *   rollback, PARALLEL:  y = [b]                           (the padded candidate, ragged)

@@ -12,14 +12,14 @@ char* error_buffer()
     return buf;
 }
 
-extern int g_attn_chunk_override;
-extern int g_lm_kernel;
-extern int g_lm_kernel_waves;
-extern int g_attn_plan;
-extern int g_attn_plan_waves;
-extern int g_attn_nr3_waves;
-extern int g_lm_packed_waves;
-extern int g_lm_packed_wide;
+extern Tunable g_attn_chunk_override;
+extern Tunable g_lm_kernel;
+extern Tunable g_lm_kernel_waves;
+extern Tunable g_attn_plan;
+extern Tunable g_attn_plan_waves;
+extern Tunable g_attn_nr3_waves;
+extern Tunable g_lm_packed_waves;
+extern Tunable g_lm_packed_wide;
 
 }  // namespace specv
 

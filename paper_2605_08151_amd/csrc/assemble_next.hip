@@ -1,8 +1,8 @@
 // spec_assemble_next: the candidates y_{n+1} of the next verification round, built on the device from what
 // spec_accept left (paper, Method, "Execution in ordinary mode" / "Execution in parallel mode":
 // eqs. ordinary_rollback_seq, ordinary_stable_seq, parallel_stable_seq, parallel_rollback_pad; Appendix
-// "Target side", eq. target_suffix_reuse; "Rollback-Based Mode Selection": a request is in the rollback set if
-// its prefix was rejected or its prepared continuation is invalidated by the verification result).
+// "Target side", eq. target_suffix_reuse; "Rollback-Based Mode Selection": the rollback set holds the requests
+// whose verified drafts were not all accepted or whose prepared continuation no longer fits the outcome).
 //
 // Integer-only and tiny: one workgroup walks the requests in blocks of 1024; a block scan of the row counts
 // gives every request its place in the ragged output, so the layout does not depend on thread timing.

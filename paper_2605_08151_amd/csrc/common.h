@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -40,17 +41,37 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the device's copy of the code) and
-// again whenever a launch needs more.  `granted` is the caller's static table, one slot per device ordinal.
+// A launch heuristic that spec_set_tuning may override: one word, written and read atomically.
+typedef std::atomic<int> Tunable;
+
 constexpr int kMaxDevices = 64;
-inline int ensure_dynamic_lds(const void* kernel, size_t bytes, size_t (&granted)[kMaxDevices], const char* who)
+
+// Compute units of the current device (256 if the runtime cannot say), cached per device ordinal.
+inline int device_cu_count()
+{
+    static std::atomic<int> cached[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    int cus = cached[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        cached[dev].store(cus, std::memory_order_relaxed);
+    }
+    return cus;
+}
+
+// Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the device's copy of the code) and
+// again whenever a launch needs more.  `granted` is the caller's static table, one slot per device ordinal; two
+// threads that race here both set the attribute, which is harmless.
+typedef std::atomic<size_t> LdsGrantTable[kMaxDevices];
+inline int ensure_dynamic_lds(const void* kernel, size_t bytes, LdsGrantTable& granted, const char* who)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
-    if (granted[dev] >= bytes) return SPEC_OK;
+    if (granted[dev].load(std::memory_order_acquire) >= bytes) return SPEC_OK;
     if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
         return fail(SPEC_EHIP, "%s: cannot reserve %zu bytes of LDS", who, bytes);
-    granted[dev] = bytes;
+    granted[dev].store(bytes, std::memory_order_release);
     return SPEC_OK;
 }
 
@@ -70,10 +91,11 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
 // Written as inline assembly so that the compiler does not order it against later LDS reads by draining
 // the whole load queue: the kernel double-buffers and waits with explicit s_waitcnt vmcnt(n) instead.
+// M0 (the LDS base of the transfer) is an operand tied to that register: the compiler writes it and knows it is live.
 __device__ inline void lds_dma16(const void* g, void* lds_base)
 {
     const uint32_t m0v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_base;
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0v) : "memory");
+    asm volatile("global_load_lds_dwordx4 %0, off" ::"v"(g), "{m0}"(m0v) : "memory");
 }
 
 }  // namespace specv

@@ -473,7 +473,7 @@ static int launch_big(const uint16_t* a, const uint16_t* w, float* c, int M, int
 {
     constexpr int BM = 64 * TMW;
     const size_t smem = (size_t)kBigStages * (BM + kBigBN) * kBigBK * 2;
-    static size_t granted[kMaxDevices] = {};
+    static LdsGrantTable granted = {};
     if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_big_kernel<TMW, NW>), smem, granted, "spec_lm_head")) return rc;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (V + kBigBN - 1) / kBigBN;
     const long grid = (long)((tiles_n + 7) / 8) * 8 * tiles_m;
@@ -610,7 +610,7 @@ static int launch_big2(const uint16_t* a, const uint16_t* w, float* c, int M, in
 {
     constexpr int BM = 64 * TMW;
     const size_t smem = 2 * (size_t)(BM + kBigBN) * kB2BK * 2;
-    static size_t granted[kMaxDevices] = {};
+    static LdsGrantTable granted = {};
     if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_big2_kernel<TMW, NW>), smem, granted, "spec_lm_head")) return rc;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (V + kBigBN - 1) / kBigBN;
     const long grid = (long)((tiles_n + 7) / 8) * 8 * tiles_m;
@@ -618,25 +618,11 @@ static int launch_big2(const uint16_t* a, const uint16_t* w, float* c, int M, in
     return SPEC_OK;
 }
 
-int g_lm_kernel_waves = 8;  // benchmark hook: waves per workgroup of the MFMA-bound kernel (4 or 8)
-int g_lm_kernel = 0;   // benchmark hook: 0 = automatic, 1 = weight-streaming, 2 = MFMA-bound with direct loads, 3 = plain tiled,
+Tunable g_lm_kernel_waves{8};  // benchmark hook: waves per workgroup of the MFMA-bound kernel (4 or 8)
+Tunable g_lm_kernel{0};   // benchmark hook: 0 = automatic, 1 = weight-streaming, 2 = MFMA-bound with direct loads, 3 = plain tiled,
                        // 8 = MFMA-bound with register staging (the automatic choice for M > 160),
                        // 4 = weight-streaming with 8 waves (4 x 2) and a 2-slab ring, 5/6/7 = 4 waves with
                        // 4-slab ring / 4-slab ring + paired refills / 2-slab ring + paired refills (the default)
-
-static int device_cu_count()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-    }
-    return cus;
-}
 
 // vocabulary entries per workgroup and the grid of the weight-streaming kernel
 static void skinny_geometry(int V, int* cols, int* grid)
@@ -654,7 +640,7 @@ static int launch_skinny(const uint16_t* a, const uint16_t* w, float* c, int M, 
 {
     constexpr int BM = (TM + MS - 1) / MS * MS * 16;
     const size_t smem = 2 * (size_t)BM * kHPitch;
-    static size_t granted[kMaxDevices] = {};
+    static LdsGrantTable granted = {};
     if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_skinny_kernel<TM, MS, RS, PAIR, STATS>), smem, granted, "spec_lm_head")) return rc;
     int cols, grid;
     skinny_geometry(V, &cols, &grid);

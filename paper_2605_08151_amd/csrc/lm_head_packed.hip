@@ -330,16 +330,14 @@ __global__ __launch_bounds__(64 * NW, 1) void lm_head_packed_kernel(
     }
 }
 
-int g_lm_packed_wide = 0;      // benchmark hook: 512-entry passes for M <= 160 (0 = automatic, 1 = always, 2 = never)
-int g_lm_packed_waves = 8;     // benchmark hook: waves per workgroup of the packed kernel (4 or 8)
+Tunable g_lm_packed_wide{0};      // benchmark hook: 512-entry passes for M <= 160 (0 = automatic, 1 = always, 2 = never)
+Tunable g_lm_packed_waves{8};     // benchmark hook: waves per workgroup of the packed kernel (4 or 8)
 
 // panel ranges and panels per range of a launch: ranges is a multiple of 8 (one per XCD and step of the dealing), as many
 // as there are CUs per row group; trailing ranges without panels are dropped 8 at a time
 static void packed_geometry(int V, int groups, int* ranges, int* per_range)
 {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        cus = 256;
+    const int cus = device_cu_count();
     const int n_panels = (V + 15) / 16;
     const int r0 = max(8, cus / groups / 8 * 8);
     *per_range = (n_panels + r0 - 1) / r0;
@@ -352,7 +350,7 @@ static int launch_packed(const uint16_t* a, const uint16_t* wp, float* c, int M,
 {
     constexpr int BM = TM * 16;
     const size_t smem = 2 * (size_t)BM * kPkHPitch + NW * 16 * (TN * 64 + 16) + (STATS ? (size_t)BM * NW * 8 : 0);
-    static size_t granted[kMaxDevices] = {};
+    static LdsGrantTable granted = {};
     if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_packed_kernel<TM, RS, NW, NT, TN, STATS>), smem, granted, "spec_lm_head_packed")) return rc;
     int ranges, per_range;
     packed_geometry(V, groups, &ranges, &per_range);

@@ -618,21 +618,7 @@ __global__ __launch_bounds__(256) void verify_attn_combine_rows_kernel(AttnParam
     }
 }
 
-int g_attn_chunk_override = 0;
-
-static int attn_cu_count()
-{
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
-    }
-    return cus;
-}
+Tunable g_attn_chunk_override{0};
 
 // Keys per kv split.  A split costs a prologue (Q to LDS), an epilogue (cross-wave merge) and a partial
 // that the merge kernel re-reads, so requests are only split when there are too few (request, kv head)
@@ -640,12 +626,13 @@ static int attn_cu_count()
 static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
 {
     long target;
-    if (g_attn_chunk_override > 0) {
-        target = g_attn_chunk_override;
+    const int forced = g_attn_chunk_override;
+    if (forced > 0) {
+        target = forced;
     } else {
         // about one workgroup per CU when every request is as long as the bound (measured best on MI355X for
         // B=8 x 64k, B=64 x 4k and B=256 x 32k lognormal alike); shorter requests simply get fewer splits
-        const long units = (long)B * Hkv, cus = attn_cu_count();
+        const long units = (long)B * Hkv, cus = device_cu_count();
         target = units * (long)max_kv_len / cus;
         if (target < 512) target = 512;
         if (target > 4096) target = 4096;
@@ -655,13 +642,13 @@ static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
     return (int)((target + step_keys - 1) / step_keys * step_keys);
 }
 
-int g_attn_nr3_waves = 8;  // benchmark hook: waves per workgroup when a request has 3 row tiles (8, or 4 with two K/V buffers each)
+Tunable g_attn_nr3_waves{8};  // benchmark hook: waves per workgroup when a request has 3 row tiles (8, or 4 with two K/V buffers each)
 static int attn_waves(int NR) { return NR <= 2 || (NR == 3 && g_attn_nr3_waves == 8) ? 8 : 4; }      // 8 waves need <= 256 registers per lane
 
 // Balanced work list (verify_attn_plan_kernel): used when requests are long enough for a few microseconds of
 // planning to pay, numerous enough for their length spread to matter, and the fixed chunk would split them anyway.
-int g_attn_plan = 0;          // benchmark hook: 0 = automatic, 1 = always (B <= 1024), 2 = never
-int g_attn_plan_waves = 0;    // benchmark hook: work items per CU the plan aims at, 0 = automatic
+Tunable g_attn_plan{0};          // benchmark hook: 0 = automatic, 1 = always (B <= 1024), 2 = never
+Tunable g_attn_plan_waves{0};    // benchmark hook: work items per CU the plan aims at, 0 = automatic
 constexpr int kPlanMinChunk = 512, kPlanMaxChunk = 8192;
 
 struct AttnPlanCfg {
@@ -675,7 +662,7 @@ static AttnPlanCfg attn_plan_cfg(int B, int Hq, int Hkv, int max_kv_len, int max
     AttnPlanCfg c{};
     c.step_keys = attn_waves(NR) * 32;
     const bool splits_anyway = chunk_target < max_kv_len;
-    const long cus = attn_cu_count();
+    const long cus = device_cu_count();
     // Pays when many requests of unknown, possibly very different lengths share the chip (measured on MI355X,
     // 256 requests of 256..32768 keys: 264 -> 213 us).  A few long requests are cut finely by the fixed chunk
     // anyway and run at the memory system's rate either way (8 x 32k..64k: 52 us without, 57 with the list).
@@ -683,7 +670,8 @@ static AttnPlanCfg attn_plan_cfg(int B, int Hq, int Hkv, int max_kv_len, int max
            (g_attn_plan == 1 || (splits_anyway && max_kv_len >= 8192 && (long)B * Hkv * 4 >= cus));
     // one workgroup is resident per CU (LDS): few requests are cut to exactly one round of equal items,
     // many requests to about two rounds, which the longest-first order packs
-    const int per_cu = g_attn_plan_waves > 0 ? g_attn_plan_waves : ((long)B * Hkv * 2 <= cus ? 1 : 2);
+    const int plan_waves = g_attn_plan_waves;
+    const int per_cu = plan_waves > 0 ? plan_waves : ((long)B * Hkv * 2 <= cus ? 1 : 2);
     long t = cus * per_cu / Hkv;
     if (t < 1) t = 1;
     c.target_items = (int)t;
@@ -708,7 +696,7 @@ template <int NR, int NW, int NBUF, bool FINAL>
 static int launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t s)
 {
     const size_t smem = attn_smem_bytes(NR, NW, NBUF, p.chunk_target < p.max_kv_len ? p.chunk_target : p.max_kv_len);
-    static size_t granted[kMaxDevices] = {};
+    static LdsGrantTable granted = {};
     if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&verify_attn_kernel<NR, NW, NBUF, FINAL>), smem, granted,
                                     "spec_verify_attn")) return rc;
     hipLaunchKernelGGL((verify_attn_kernel<NR, NW, NBUF, FINAL>), grid, dim3(NW * 64), smem, s, p);

@@ -218,3 +218,59 @@ def test_accept_test_uses_uniform_j_tag0(oracle):
         if u >= 0.5:
             assert res["out_tokens"][0, 0] == 0               # residual removes the rejected token
     assert 150 < n_acc < 350
+
+
+def _bucket(u, edges):
+    """Index of the inverse-CDF bucket of u, or None when u is within 1e-6 of an edge."""
+    for k, e in enumerate(edges):
+        if abs(u - e) < 1e-6:
+            return None
+        if u < e:
+            return k
+    return len(edges)
+
+
+def test_zero_residual_falls_back_to_the_target_distribution(oracle):
+    """p = (1/2, 1/4, 1/4, 0) exactly, the draft is the masked entry 3 and q = p there and elsewhere: the accept
+    test 0 < 0 fails, max(0, p - q) is zero everywhere, so the bonus is the inverse-CDF bucket of
+    U(seed, round, 1, 1) in p itself: never the rejected token, never -1."""
+    row = np.log(np.array([2.0, 1.0, 1.0, 1.0])).astype(np.float32)
+    row[3] = -np.inf
+    logits = np.stack([row, np.zeros(4, np.float32)])
+    q = oracle.target_probs(row, 1.0)[None, :].copy()
+    assert list(q[0]) == [0.5, 0.25, 0.25, 0.0]
+    hits = set()
+    for seed in range(1500):
+        res = oracle.accept(logits, np.array([0, 3], np.int32), q, np.ones(1, np.float32),
+                            np.array([seed], np.uint64), 7, _qo([1]), 1)
+        assert res["accept_len"][0] == 0 and res["rollback"][0] == 1 and res["status"] == 0
+        want = _bucket(oracle.uniform(seed, 7, 1, 1), [0.5, 0.75])
+        if want is not None:
+            assert res["out_tokens"][0, 0] == want
+            hits.add(want)
+        assert list(res["out_tokens"][0, 1:]) == [-1]
+    assert hits == {0, 1, 2}
+
+
+def test_drafter_above_target_everywhere_rejects_into_the_target_distribution(oracle):
+    """q = 2p (a drafter whose stated probabilities exceed the target's at every token): draft d is accepted
+    iff U(seed, round, 1, 0) < 1/2; a rejection leaves no positive residual, and the bonus is then the bucket
+    of U(seed, round, 1, 1) in p = (1/2, 1/4, 1/4)."""
+    row = np.log(np.array([2.0, 1.0, 1.0])).astype(np.float32)
+    logits = np.stack([row, row])
+    q = (2.0 * oracle.target_probs(row, 1.0))[None, :].astype(np.float32)
+    n_rej = 0
+    for seed in range(1200):
+        d = seed % 3
+        res = oracle.accept(logits, np.array([0, d], np.int32), q, np.ones(1, np.float32),
+                            np.array([seed], np.uint64), 2, _qo([1]), 1)
+        u = oracle.uniform(seed, 2, 1, 0)
+        if abs(u - 0.5) < 1e-6:
+            continue
+        assert res["accept_len"][0] == int(u < 0.5)
+        if u >= 0.5:
+            n_rej += 1
+            want = _bucket(oracle.uniform(seed, 2, 1, 1), [0.5, 0.75])
+            if want is not None:
+                assert res["out_tokens"][0, 0] == want
+    assert 400 < n_rej < 800
