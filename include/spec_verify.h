@@ -399,6 +399,21 @@ int spec_kv_commit_tree(void* k_cache, void* v_cache, int32_t* page_table, int m
                         int32_t* free_list, int32_t free_capacity, int32_t* free_count,
                         int B, int Hkv, int D, int page_size, int32_t* status_flags, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Measurement probes (not part of the verification path; no passage of the paper defines them).  They give the
+ * ceilings this particular chip reaches, for reports that quote a kernel against the measured roof as well as
+ * against the datasheet.  Asynchronous on stream; time them with events on that stream.
+ *   spec_probe_read: reads `bytes` bytes at src (device, 16-byte aligned, bytes % 16 == 0) exactly once, linearly;
+ *     sink (device, >= 4 bytes) is practically never written.  SPEC_EINVAL on misuse.
+ *   spec_probe_mfma: one workgroup of 8 waves per compute unit, each wave `iters` x 16 independent
+ *     v_mfma_f32_16x16x32_bf16 on register operands (random bit patterns, or all equal when constant_operands != 0:
+ *     the chip's power limit makes the two differ).  Returns the floating-point operations of the launch as a
+ *     double (> 0), or -1 on misuse.  sink: device, >= 4 bytes, practically never written.
+ * ------------------------------------------------------------------------- */
+int spec_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+
+double spec_probe_mfma(int iters, int constant_operands, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,6 +23,7 @@ EXPORTS = (
     "spec_verify_attn_tree", "spec_accept_tree", "spec_kv_commit_tree",
     "spec_lm_head_packed_bytes", "spec_lm_head_pack", "spec_lm_head_packed",
     "spec_lm_head_packed_stats_blocks", "spec_lm_head_packed_stats",
+    "spec_probe_read", "spec_probe_mfma",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -89,6 +90,10 @@ def _load():
     lib.spec_compress_prompts.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.spec_assemble_next.restype = i32
     lib.spec_assemble_next.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.spec_probe_read.restype = i32
+    lib.spec_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.spec_probe_mfma.restype = ctypes.c_double
+    lib.spec_probe_mfma.argtypes = [i32, i32, vp, vp]
     lib.spec_next_mode.restype = i32
     lib.spec_next_mode.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                    ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -317,3 +322,15 @@ def spec_kv_commit_tree(k_cache, v_cache, page_table, seq_lens, qo_indptr, accep
         _ptr(path, torch.int32), path.shape[1] - 1, _ptr(free_list, torch.int32), free_list.shape[0],
         _ptr(free_count, torch.int32), B, Hkv, D, P, _ptr(status_flags, torch.int32), _stream()))
 
+
+
+def spec_probe_read(src, sink):
+    """Linear read of the whole tensor `src`, once."""
+    _check(_lib.spec_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()))
+
+
+def spec_probe_mfma(iters, constant_operands, sink):
+    """MFMA-only loop; returns the floating-point operations of the launch."""
+    flops = float(_lib.spec_probe_mfma(int(iters), int(bool(constant_operands)), _ptr(sink), _stream()))
+    _check(0 if flops > 0 else -1)
+    return flops

@@ -167,6 +167,71 @@ def test_attention_needle_and_causality(sv, oracle):
     _close(out.float().cpu().numpy(), _oracle_attn(oracle, b), "needle")
 
 
+def _split_geometry(length, target):
+    """(splits, keys per split) of a request of `length` keys when splits are at most `target` keys long."""
+    ns = -(-length // target)
+    return ns, (-(-length // ns) + 15) // 16 * 16
+
+
+@pytest.mark.parametrize("mode", ["fixed_4096", "work_list"])
+def test_long_context_sharp_data_and_needles(sv, oracle, mode):
+    """Contexts of 32k-40k keys on permuted pages, unit-variance Q/K/V (a peaked softmax: one page is visible),
+    with the fixed 4096-key split (256 page ids staged per workgroup) and with the device-built work list.
+    Then the same batch with a handful of dominant keys, each carrying its own value pattern, placed in
+    several splits, on both sides of a split boundary, at the end of a split, in the last partial page and inside
+    the candidate block: a page fetched from the wrong place or left out changes the mean of the patterns."""
+    cfg = wl.VerifyConfig("long_sharp", 61, 2, (4,), ("uniform", 32768, 40000), 8, 1, 64, 64, sigma_qkv=1.0)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    tuning = {"attn_plan": 2, "attn_chunk": 4096} if mode == "fixed_4096" else {"attn_plan": 1}
+    for k, v in tuning.items():
+        sv.spec_set_tuning(k, v)
+    try:
+        step = _step(b, cfg)
+        run = lambda: step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
+        out = run()
+        torch.cuda.synchronize()
+        ref, ref_lse = _oracle_attn(oracle, b, want_lse=True)
+        _close(out.float().cpu().numpy(), ref, f"{mode} sharp", sharp=True)
+        np.testing.assert_allclose(step.lse.cpu().numpy(), ref_lse, rtol=2e-3, atol=2e-3)
+
+        # needles
+        direction = torch.ones(cfg.D, device="cuda") / math.sqrt(cfg.D)
+        b["q"][:] = (8.0 * direction).to(torch.bfloat16)
+        gen = torch.Generator().manual_seed(5)
+        pt = b["page_table"].cpu()
+        placed = []
+        for i, c in enumerate(b["ctx"].tolist()):
+            length = c + 5
+            spots = {5, c - 1, c + 1, length - 1}                   # first page, last committed key, a candidate, the last key
+            for target in (4096, 512):
+                ns, chunk = _split_geometry(length, target)
+                for sp in (1, ns // 2, ns - 1):
+                    kbeg, kend = sp * chunk, min(length, (sp + 1) * chunk)
+                    if 0 < kbeg < kend:
+                        spots |= {kbeg - 1, kbeg, kend - 1}
+            for t in sorted(spots):
+                page = int(pt[i, t // 16])
+                pattern = (torch.randint(0, 2, (cfg.D,), generator=gen) * 2 - 1).to(torch.float32) * 4.0
+                b["k_cache"][page, 0, t % 16] = (64.0 * direction).to(torch.bfloat16)
+                b["v_cache"][page, 0, t % 16] = pattern.to(torch.bfloat16).cuda()
+                placed.append((i, t, pattern.numpy()))
+        out = run()
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy()
+        ref = _oracle_attn(oracle, b)
+        _close(got, ref, f"{mode} needles", sharp=True)
+        # independent of the oracle: every row is the plain mean of the patterns it may see
+        qo = b["qo_indptr"].cpu().numpy()
+        for i, c in enumerate(b["ctx"].tolist()):
+            for j in range(5):
+                seen = np.stack([pat for (ii, t, pat) in placed if ii == i and t <= c + j])
+                np.testing.assert_allclose(got[qo[i] + j], np.broadcast_to(seen.mean(0), (8, cfg.D)), atol=0.04)
+        assert int(step.status.cpu()) == 0
+    finally:
+        for k in tuning:
+            sv.spec_set_tuning(k, 0)
+
+
 def test_attention_flags_bad_inputs_without_faulting(sv, oracle):
     cfg = wl.VerifyConfig("bad", 14, 3, (2,), ("uniform", 40, 90), 8, 1, 64, 64, sigma_qkv=1.0)
     b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
@@ -410,6 +475,65 @@ def test_stochastic_one_hot_drafter_and_q_equal_p(sv, oracle):
     got, ref = _accept_both(sv, oracle, logits, tokens, dp, temp, seeds, 1, qo, 4)
     _assert_same(got, ref, gammas)
     assert (got["accept_len"] == 4).all()
+
+
+@pytest.mark.parametrize("V", [5, 10000, 151936])
+def test_sampler_without_positive_residual_draws_from_the_target(sv, oracle, V):
+    """A rejected draft whose residual max(0, p - q) is zero everywhere: (a) the draft is a masked entry (-inf logit)
+    and q equals p, so 0 < 0 rejects it; (b) q = 2p, rejected whenever u >= 1/2.  The bonus then comes from p
+    itself.  One and several 4096-entry segments; integers identical to the oracle's."""
+    rng = np.random.default_rng(V + 17)
+    B = 40
+    gammas = np.full(B, 2)
+    qo = _qo(gammas)
+    logits = rng.normal(0, 1.5, (qo[-1], V)).astype(np.float32)
+    tokens = rng.integers(0, V, qo[-1]).astype(np.int32)
+    dp = np.zeros((qo[-1] - B, V), np.float32)
+    for i in range(B):
+        r0 = qo[i]
+        masked_at = 1 + (i % 2)                                  # the draft that hits the masked entry (even i: the first)
+        d = int(tokens[r0 + masked_at])
+        logits[r0 + masked_at - 1, d] = -np.inf
+        for j in (1, 2):
+            p = oracle.target_probs(logits[r0 + j - 1], 0.9)
+            dp[r0 - i + j - 1] = p if i % 4 < 2 else 2.0 * p       # (b) for half of the requests
+        if masked_at == 2:                                       # a first draft that q == p accepts: any token with p > 0
+            tokens[r0 + 1] = int(np.argmax(logits[r0]))
+    seeds = rng.integers(0, 2 ** 63, B, dtype=np.uint64)
+    temp = np.full(B, 0.9, np.float32)
+    got, ref = _accept_both(sv, oracle, logits, tokens, dp, temp, seeds, 11, qo, 2)
+    _assert_same(got, ref, gammas)
+    assert got["status"] == 0
+    al = ref["accept_len"]
+    assert (al[0::4] == 0).all() and (al[1::4] == 1).all()      # q == p: rejected exactly at the masked draft
+    assert (al < 2).all() and (ref["out_tokens"][np.arange(B), al] >= 0).all()
+    for i in range(B):                                           # rejected at the masked draft: the bonus is never that entry
+        if al[i] == i % 2:
+            assert ref["out_tokens"][i, al[i]] != tokens[qo[i] + 1 + (i % 2)]
+
+
+def test_sampler_fallback_bucket_across_segments(sv, oracle):
+    """p = (1/2, 1/4, 1/4) on entries 10, 5000 and 9000 of a 10000-entry row (three different segments), every
+    other entry masked; the draft is a masked entry and q = p: the bonus is the bucket of U(seed, round, 1, 1)."""
+    V, B = 10000, 64
+    row = np.full(V, -np.inf, np.float32)
+    row[[10, 5000, 9000]] = np.log(np.array([2.0, 1.0, 1.0])).astype(np.float32)
+    qo = _qo(np.full(B, 1))
+    logits = np.tile(np.stack([row, row]), (B, 1))
+    tokens = np.tile(np.array([0, 7777], np.int32), B)
+    dp = np.tile(oracle.target_probs(row, 1.0)[None, :], (B, 1))
+    seeds = np.arange(100, 100 + B, dtype=np.uint64)
+    got, ref = _accept_both(sv, oracle, logits, tokens, dp, np.ones(B, np.float32), seeds, 4, qo, 1)
+    _assert_same(got, ref, np.full(B, 1))
+    assert (got["accept_len"] == 0).all()
+    hits = set()
+    for i in range(B):
+        u = oracle.uniform(int(seeds[i]), 4, 1, 1)
+        want = None if min(abs(u - 0.5), abs(u - 0.75)) < 1e-6 else 10 if u < 0.5 else 5000 if u < 0.75 else 9000
+        if want is not None:
+            assert got["out_tokens"][i, 0] == want
+            hits.add(want)
+    assert hits == {10, 5000, 9000}
 
 
 def test_accept_flags_bad_rows_and_tokens(sv, oracle):
@@ -1156,24 +1280,16 @@ def test_full_size_configuration(sv, oracle, name):
 
 def test_full_size_hybrid_mix_properties(sv, oracle):
     """The hybrid workload (B=256, gamma in {0,2,4,8}, lognormal contexts up to 32k, half sampled):
-    attention is checked on a sample of requests the oracle recomputes (all their rows and heads),
-    acceptance and commit are bit-exact on the whole batch."""
+    attention of the whole batch against the oracle (the device-built work list at full size), logits on
+    sampled vocabulary entries, acceptance and commit bit-exact on the whole batch."""
     cfg = wl.CONFIGS["hybrid"]
     b = wl.make_batch(cfg, device="cuda")
     step = _step(b, cfg)
     out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
     torch.cuda.synchronize()
     qo = b["qo_indptr"].cpu().numpy()
-    ctx = b["ctx"].numpy()
-    order = np.argsort(ctx)
-    pick = np.unique(np.concatenate([order[:3], order[-2:], np.random.default_rng(0).integers(0, cfg.B, 8)]))
-    rows = np.concatenate([np.arange(qo[i], qo[i + 1]) for i in pick])
-    sub_qo = np.zeros(len(pick) + 1, np.int32)
-    sub_qo[1:] = np.cumsum([qo[i + 1] - qo[i] for i in pick])
-    ref = oracle.verify_attn(wl.bf16_bits(b["q"][torch.from_numpy(rows).cuda()]), wl.bf16_bits(b["k_cache"]),
-                             wl.bf16_bits(b["v_cache"]), b["page_table"].cpu().numpy()[pick].copy(),
-                             b["seq_lens"].cpu().numpy()[pick].copy(), sub_qo, b["scale"])
-    _close(out.float().cpu().numpy()[rows], ref, "hybrid attn sample")
+    ref = _oracle_attn(oracle, b)                        # all 256 requests, every row and head (a few seconds of host time)
+    _close(out.float().cpu().numpy(), ref, "hybrid attn, whole batch")
     assert int(step.status.cpu()) == 0
     del ref, out
     # acceptance + commit on the whole batch
