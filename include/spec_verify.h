@@ -240,6 +240,23 @@ int spec_accept(const float* logits, const int32_t* tokens, const float* draft_p
                 int32_t* status_flags,
                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* spec_accept_static — spec_accept for callers that cannot allocate device memory or hand in a workspace: code
+ * recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without
+ * workspace), same kernels, same outputs, flags and errors as spec_accept; the scratch is a 4 MiB array inside
+ * the library image, one copy per GPU, held until the process ends.  Allocates nothing.
+ *   Limit: spec_accept_workspace_bytes(B, M, V, gamma_max) <= 4 MiB (e.g. M = 1206 rows x V = 151936 needs 1.1 MiB);
+ *   beyond it SPEC_EWORKSPACE with the sizes in the error text, and nothing is enqueued.
+ *   All calls on one GPU share that GPU's array, which keeps the previous call's contents (no part of it has to
+ *   be cleared: each call overwrites what it reads): calls that overlap in time on one GPU, on different
+ *   streams, race and must be ordered by the caller.  The first call on each device resolves the array's device
+ *   address (one hipGetSymbolAddress, no allocation); make it outside stream capture. */
+int spec_accept_static(const float* logits, const int32_t* tokens, const float* draft_probs,
+                       const float* temperature, const uint64_t* seeds, uint32_t round,
+                       const int32_t* qo_indptr,
+                       int32_t* accept_len, int32_t* out_tokens, uint8_t* rollback, int32_t* stats,
+                       int B, int M, int V, int gamma_max,
+                       int32_t* status_flags, void* stream);
+
 /* spec_accept with the block statistics of spec_lm_head_stats (blk_max, blk_arg, blocks as described there;
  * blocks == 0: identical to spec_accept).  Requests with temperature 0 take their row maxima from the
  * statistics; the logits of their rows are not read.  Sampled requests are handled as in spec_accept.  With

@@ -23,7 +23,7 @@ EXPORTS = (
     "spec_verify_attn_tree", "spec_accept_tree", "spec_kv_commit_tree",
     "spec_lm_head_packed_bytes", "spec_lm_head_pack", "spec_lm_head_packed",
     "spec_lm_head_packed_stats_blocks", "spec_lm_head_packed_stats",
-    "spec_probe_read", "spec_probe_mfma",
+    "spec_probe_read", "spec_probe_mfma", "spec_accept_static",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -57,6 +57,8 @@ def _load():
     lib.spec_accept_workspace_bytes.argtypes = [i32] * 4
     lib.spec_accept.restype = i32
     lib.spec_accept.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.spec_accept_static.restype = i32
+    lib.spec_accept_static.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
     lib.spec_kv_commit.restype = i32
     lib.spec_kv_commit.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp]
     lib.spec_lm_head_stats_blocks.restype = i32
@@ -239,6 +241,18 @@ def spec_accept(logits, tokens, draft_probs, temperature, seeds, round_, qo_indp
         _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), _ptr(rollback, torch.uint8),
         _ptr(stats, torch.int32), B, M, V, int(gamma_max), _ptr(status_flags, torch.int32),
         _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
+
+
+def spec_accept_static(logits, tokens, draft_probs, temperature, seeds, round_, qo_indptr, accept_len, out_tokens, rollback,
+                       stats, gamma_max, status_flags):
+    M, V = logits.shape
+    B = qo_indptr.shape[0] - 1
+    assert tuple(out_tokens.shape) == (B, gamma_max + 1)
+    _check(_lib.spec_accept_static(
+        _ptr(logits, torch.float32), _ptr(tokens, torch.int32), _ptr(draft_probs, torch.float32),
+        _ptr(temperature, torch.float32), _ptr(seeds, torch.int64), int(round_), _ptr(qo_indptr, torch.int32),
+        _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), _ptr(rollback, torch.uint8),
+        _ptr(stats, torch.int32), B, M, V, int(gamma_max), _ptr(status_flags, torch.int32), _stream()))
 
 
 def spec_accept_stats(logits, tokens, draft_probs, temperature, seeds, round_, qo_indptr, accept_len, out_tokens, rollback,

@@ -691,6 +691,51 @@ extern "C" int spec_accept(const float* logits, const int32_t* tokens, const flo
                              workspace_bytes, stream);
 }
 
+// ---- spec_accept for callers that cannot allocate: the scratch lives in the library image -----------------------
+// One array per GPU (every device that loads the code object holds its own copy at its own address) for as long as
+// the process lives.  Nothing in it has to start at zero: every kernel of the call writes what a later one reads.
+namespace specv {
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of this GPU's copy of `scratch`, resolved once per device with that device current.  The array's
+// name is only a host-side handle: kernels must be given the address looked up here.
+static int static_scratch(void** out)
+{
+    static std::atomic<void*> resolved[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return fail(SPEC_EHIP, "spec_accept_static: no current device (or ordinal beyond %d)", kMaxDevices - 1);
+    void* ptr = resolved[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(SPEC_EHIP, "spec_accept_static: cannot resolve the scratch array on device %d: %s", dev, hipGetErrorString(e));
+        resolved[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return SPEC_OK;
+}
+}  // namespace specv
+
+extern "C" int spec_accept_static(const float* logits, const int32_t* tokens, const float* draft_probs,
+                                  const float* temperature, const uint64_t* seeds, uint32_t round,
+                                  const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
+                                  uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                                  int32_t* status_flags, void* stream)
+{
+    using namespace specv;
+    const size_t need = spec_accept_workspace_bytes(B, M, V, gamma_max);
+    if (need > kStaticScratchBytes)
+        return fail(SPEC_EWORKSPACE, "spec_accept_static: B=%d M=%d V=%d needs %zu bytes of scratch, the built-in array holds %zu; "
+                    "use spec_accept with a workspace", B, M, V, need, kStaticScratchBytes);
+    void* ptr = nullptr;
+    if (int rc = static_scratch(&ptr)) return rc;
+    return spec_accept_stats(logits, tokens, draft_probs, temperature, seeds, round, qo_indptr, accept_len, out_tokens,
+                             rollback, stats, B, M, V, gamma_max, nullptr, nullptr, 0, status_flags, ptr,
+                             kStaticScratchBytes, stream);
+}
+
 extern "C" int spec_accept_tree(const float* logits, const int32_t* tokens, const int32_t* parent,
                                 const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens, int32_t* path,
                                 uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
