@@ -84,6 +84,10 @@ int spec_version(void);
  *   "lm_packed_waves"  waves per workgroup of the weight-streaming kernel of spec_lm_head_packed: 4 or 8 (default).
  *   "lm_packed_wide"   that kernel with passes of 512 vocabulary entries over row groups of at most 80 rows:
  *                      0 = automatic (off), 1 = always, 2 = never.
+ *   "lm_packed_tile"   which kernel spec_lm_head_packed runs for M > 160: 0 = automatic (the large-tile MFMA-bound
+ *                      kernel), 1 = the weight-streaming kernel over row groups of at most 160 rows.
+ *   "lm_mfma_rows"     rows per row group of that large-tile kernel at most, 144..256; 0 = automatic.
+ *   "lm_mfma_nt"       its logits stores nontemporal: 0 = automatic (one or two row groups), 1 = always, 2 = never.
  * A forced kernel that cannot take the shape falls back to the plain tiled one.  Unknown key: SPEC_EINVAL. */
 int spec_set_tuning(const char* key, int value);
 
@@ -181,8 +185,8 @@ int spec_lm_head_stats(const void* hidden, const void* W, float* logits, int M, 
  *   spec_lm_head_pack: W [V, H] bf16 row-major -> Wp; H % 32 == 0 (SPEC_ESHAPE).
  *   spec_lm_head_packed: hidden [M, H] bf16, logits [M, V] fp32; H % 256 == 0
  *   (SPEC_ESHAPE otherwise); any M (above 160 rows the batch is cut into
- *   equal row groups that stream the same panels at the same time on one XCD,
- *   so that HBM still sees Wp once) and any V.
+ *   row groups of at most 256 rows that stream the same panels at the same
+ *   time on one XCD, so that HBM still sees Wp once) and any V.
  * Both are asynchronous on the stream and allocate nothing.
  * ------------------------------------------------------------------------- */
 size_t spec_lm_head_packed_bytes(int V, int H);
@@ -423,8 +427,9 @@ int spec_kv_commit_tree(void* k_cache, void* v_cache, int32_t* page_table, int m
  *   spec_probe_read: reads `bytes` bytes at src (device, 16-byte aligned, bytes % 16 == 0) exactly once, linearly;
  *     sink (device, >= 4 bytes) is practically never written.  SPEC_EINVAL on misuse.
  *   spec_probe_mfma: one workgroup of 8 waves per compute unit, each wave `iters` x 16 independent
- *     v_mfma_f32_16x16x32_bf16 on register operands (random bit patterns, or all equal when constant_operands != 0:
- *     the chip's power limit makes the two differ).  Returns the floating-point operations of the launch as a
+ *     v_mfma_f32_16x16x32_bf16 on register operands (random bit patterns, or all equal when bit 0 of
+ *     constant_operands is set: the chip's power limit makes the two differ; bit 1 set: the same flops as `iters` x 8
+ *     v_mfma_f32_32x32x16_bf16).  Returns the floating-point operations of the launch as a
  *     double (> 0), or -1 on misuse.  sink: device, >= 4 bytes, practically never written.
  * ------------------------------------------------------------------------- */
 int spec_probe_read(const void* src, size_t bytes, void* sink, void* stream);

@@ -345,6 +345,6 @@ def spec_probe_read(src, sink):
 
 def spec_probe_mfma(iters, constant_operands, sink):
     """MFMA-only loop; returns the floating-point operations of the launch."""
-    flops = float(_lib.spec_probe_mfma(int(iters), int(bool(constant_operands)), _ptr(sink), _stream()))
+    flops = float(_lib.spec_probe_mfma(int(iters), int(constant_operands), _ptr(sink), _stream()))
     _check(0 if flops > 0 else -1)
     return flops

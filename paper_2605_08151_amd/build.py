@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecverify.so")
-SOURCES = ["api.hip", "verify_attn.hip", "lm_head.hip", "lm_head_packed.hip", "accept.hip", "kv_commit.hip", "assemble_next.hip", "draft_side.hip", "probes.hip"]
+SOURCES = ["api.hip", "verify_attn.hip", "lm_head.hip", "lm_head_packed.hip", "lm_head_mfma.hip", "accept.hip", "kv_commit.hip", "assemble_next.hip", "draft_side.hip", "probes.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -20,6 +20,9 @@ extern Tunable g_attn_plan_waves;
 extern Tunable g_attn_nr3_waves;
 extern Tunable g_lm_packed_waves;
 extern Tunable g_lm_packed_wide;
+extern Tunable g_lm_packed_tile;
+extern Tunable g_lm_mfma_rows;
+extern Tunable g_lm_mfma_nt;
 
 }  // namespace specv
 
@@ -43,6 +46,9 @@ extern "C" int spec_set_tuning(const char* key, int value)
     if (key && std::strcmp(key, "attn_plan_waves") == 0) { specv::g_attn_plan_waves = value; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_nr3_waves") == 0) { specv::g_attn_nr3_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_packed_wide") == 0) { specv::g_lm_packed_wide = value; return SPEC_OK; }
+    if (key && std::strcmp(key, "lm_packed_tile") == 0) { specv::g_lm_packed_tile = value; return SPEC_OK; }
+    if (key && std::strcmp(key, "lm_mfma_nt") == 0) { specv::g_lm_mfma_nt = value; return SPEC_OK; }
+    if (key && std::strcmp(key, "lm_mfma_rows") == 0) { specv::g_lm_mfma_rows = value; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_packed_waves") == 0) { specv::g_lm_packed_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     return specv::fail(SPEC_EINVAL, "spec_set_tuning: unknown key '%s'", key ? key : "(null)");
 }

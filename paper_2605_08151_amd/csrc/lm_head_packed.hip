@@ -402,6 +402,9 @@ extern "C" int spec_lm_head_pack(const void* W, void* Wp, int V, int H, void* st
 
 namespace specv {
 
+extern Tunable g_lm_packed_tile;
+int lm_head_mfma_dispatch(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, hipStream_t s);
+
 static int packed_groups(int M) { return (M + kPkMaxRows - 1) / kPkMaxRows; }
 
 // shared by spec_lm_head_packed (blk_max == nullptr) and spec_lm_head_packed_stats
@@ -418,6 +421,12 @@ static int lm_head_packed_any(const char* who, const void* hidden, const void* W
         return fail(SPEC_ESHAPE, "%s: V=%d is beyond the 32-bit row offsets of the kernel", who, V);
     hipStream_t s = (hipStream_t)stream;
     const uint16_t* wp = (const uint16_t*)Wp;
+    // More than 160 rows: the contraction is bound by the matrix cores, and the large-tile kernel serves it
+    if (!blk_max && M > kPkMaxRows && g_lm_packed_tile != 1 && (size_t)V <= ((size_t)1 << 32) / (4 * (size_t)(304 + 16))) {
+        const int rc = lm_head_mfma_dispatch((const uint16_t*)hidden, wp, logits, M, H, V, s);
+        if (rc != SPEC_OK) return rc;
+        return check_launch(who);
+    }
     // More rows than a workgroup holds: the rows are cut into equal groups of at most 160 (a multiple of 16 each), and
     // the grid is groups x panel ranges.  HBM still sees W once; the other groups read it from the L2.
     int groups = packed_groups(M);

@@ -62,6 +62,45 @@ __global__ __launch_bounds__(512, 1) void probe_mfma_kernel(int iters, int const
     if (s == 12345.678f) sink[0] = s;                       // keeps the accumulators alive
 }
 
+// The same loop with v_mfma_f32_32x32x16_bf16 (8 independent accumulators of 16 registers): the same flops per
+// instruction pair, half the operand registers read per flop.
+__global__ __launch_bounds__(512, 1) void probe_mfma32_kernel(int iters, int constant_operands, uint32_t seed, float* __restrict__ sink)
+{
+    bf16x8 a[4], b[4];
+    uint32_t h = seed ^ (threadIdx.x * 0x9E3779B9u) ^ (blockIdx.x * 0x85EBCA6Bu);
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+        u32x4 wa, wb;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            h = h * 1664525u + 1013904223u;
+            const uint32_t ra = constant_operands ? 0x3F803F80u : ((h & 0x807F807Fu) | 0x3F803F80u);
+            h = h * 1664525u + 1013904223u;
+            const uint32_t rb = constant_operands ? 0x3F803F80u : ((h & 0x807F807Fu) | 0x3F803F80u);
+            wa[k] = ra;
+            wb[k] = rb;
+        }
+        a[f] = __builtin_bit_cast(bf16x8, wa);
+        b[f] = __builtin_bit_cast(bf16x8, wb);
+    }
+    f32x16 acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[k][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[k & 3], b[(k >> 1) & 3], acc[k], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[k][e];
+    if (s == 12345.678f) sink[0] = s;
+}
+
 }  // namespace specv
 
 extern "C" int spec_probe_read(const void* src, size_t bytes, void* sink, void* stream)
@@ -80,7 +119,11 @@ extern "C" double spec_probe_mfma(int iters, int constant_operands, void* sink, 
     using namespace specv;
     if (!sink || iters <= 0) { fail(SPEC_EINVAL, "spec_probe_mfma: NULL sink or iters <= 0"); return -1.0; }
     const int grid = device_cu_count();
-    hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(512), 0, (hipStream_t)stream, iters, constant_operands, 12345u, (float*)sink);
+    // bit 1 of constant_operands selects the 32x32x16 shape (8 instructions of 32768 flop per iteration instead of 16 of 16384)
+    if (constant_operands & 2)
+        hipLaunchKernelGGL(probe_mfma32_kernel, dim3(grid), dim3(512), 0, (hipStream_t)stream, iters, constant_operands & 1, 12345u, (float*)sink);
+    else
+        hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(512), 0, (hipStream_t)stream, iters, constant_operands & 1, 12345u, (float*)sink);
     if (check_launch("spec_probe_mfma") != SPEC_OK) return -1.0;
     // floating-point operations of the launch: workgroups x 8 waves x iters x 16 instructions x 2*16*16*32
     return (double)grid * 8.0 * (double)iters * 16.0 * 16384.0;

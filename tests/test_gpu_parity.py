@@ -345,6 +345,37 @@ def test_lm_head_packed_matches_oracle(sv, oracle, M, H, V, std):
         sv.spec_set_tuning("lm_packed_wide", 0)
 
 
+@pytest.mark.parametrize("M,cap", [(161, 0), (200, 0), (224, 0), (240, 0), (256, 0), (270, 0), (300, 0), (418, 0), (576, 0), (1206, 0),
+                                   (1206, 256), (500, 144), (700, 240)])
+def test_lm_head_large_tile_kernel(sv, oracle, M, cap):
+    """The MFMA-bound kernel behind spec_lm_head_packed for M > 160, at every row-tile count per group it is built for
+    (9..16, even and uneven groups, a last group with a ragged tile), vocabulary sizes with ragged panels and passes:
+    every logit against the oracle, and the same bits as the weight-streaming kernel (same k order per output)."""
+    H, V = 512, 4104 + 16 * (M % 7)
+    g = torch.Generator(device="cuda").manual_seed(M + cap)
+    hidden = torch.randn((M, H), generator=g, device="cuda").to(torch.bfloat16)
+    W = (torch.randn((V, H), generator=g, device="cuda") / math.sqrt(H)).to(torch.bfloat16)
+    Wp = torch.empty(sv.spec_lm_head_packed_bytes(V, H) // 2, dtype=torch.bfloat16, device="cuda")
+    sv.spec_lm_head_pack(W, Wp)
+    guard = 256
+    flat = torch.full((M * V + 2 * guard,), 9.0, dtype=torch.float32, device="cuda")
+    logits = flat[guard:guard + M * V].view(M, V)
+    other = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    sv.spec_set_tuning("lm_mfma_rows", cap)
+    try:
+        sv.spec_lm_head_packed(hidden, Wp, logits)
+        sv.spec_set_tuning("lm_packed_tile", 1)
+        sv.spec_lm_head_packed(hidden, Wp, other)
+        torch.cuda.synchronize()
+    finally:
+        sv.spec_set_tuning("lm_mfma_rows", 0)
+        sv.spec_set_tuning("lm_packed_tile", 0)
+    assert (flat[:guard] == 9.0).all() and (flat[-guard:] == 9.0).all()
+    assert torch.equal(logits, other)
+    ref = oracle.lm_head(wl.bf16_bits(hidden), wl.bf16_bits(W))
+    _close(logits.cpu().numpy(), ref, f"large tile M={M}", sharp=True)
+
+
 def test_lm_head_packed_rejects_bad_shapes(sv):
     hidden = torch.zeros((4, 192), dtype=torch.bfloat16, device="cuda")
     Wp = torch.zeros((sv.spec_lm_head_packed_bytes(40, 192) // 2,), dtype=torch.bfloat16, device="cuda")
