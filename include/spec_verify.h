@@ -426,6 +426,8 @@ int spec_kv_commit_tree(void* k_cache, void* v_cache, int32_t* page_table, int m
  * against the datasheet.  Asynchronous on stream; time them with events on that stream.
  *   spec_probe_read: reads `bytes` bytes at src (device, 16-byte aligned, bytes % 16 == 0) exactly once, linearly;
  *     sink (device, >= 4 bytes) is practically never written.  SPEC_EINVAL on misuse.
+ *   spec_probe_read_pages: reads the n_pages pages of 4096 bytes listed in pages[] (device int32, page p = bytes
+ *     4096 p .. 4096 p + 4095 of src), each once, in list order: the access pattern of a paged K/V cache.
  *   spec_probe_mfma: one workgroup of 8 waves per compute unit, each wave `iters` x 16 independent
  *     v_mfma_f32_16x16x32_bf16 on register operands (random bit patterns, or all equal when bit 0 of
  *     constant_operands is set: the chip's power limit makes the two differ; bit 1 set: the same flops as `iters` x 8
@@ -433,6 +435,8 @@ int spec_kv_commit_tree(void* k_cache, void* v_cache, int32_t* page_table, int m
  *     double (> 0), or -1 on misuse.  sink: device, >= 4 bytes, practically never written.
  * ------------------------------------------------------------------------- */
 int spec_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+
+int spec_probe_read_pages(const void* src, const int32_t* pages, int n_pages, void* sink, void* stream);
 
 double spec_probe_mfma(int iters, int constant_operands, void* sink, void* stream);
 

@@ -23,7 +23,7 @@ EXPORTS = (
     "spec_verify_attn_tree", "spec_accept_tree", "spec_kv_commit_tree",
     "spec_lm_head_packed_bytes", "spec_lm_head_pack", "spec_lm_head_packed",
     "spec_lm_head_packed_stats_blocks", "spec_lm_head_packed_stats",
-    "spec_probe_read", "spec_probe_mfma", "spec_accept_static",
+    "spec_probe_read", "spec_probe_read_pages", "spec_probe_mfma", "spec_accept_static",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -94,6 +94,8 @@ def _load():
     lib.spec_assemble_next.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp]
     lib.spec_probe_read.restype = i32
     lib.spec_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.spec_probe_read_pages.restype = i32
+    lib.spec_probe_read_pages.argtypes = [vp, vp, i32, vp, vp]
     lib.spec_probe_mfma.restype = ctypes.c_double
     lib.spec_probe_mfma.argtypes = [i32, i32, vp, vp]
     lib.spec_next_mode.restype = i32
@@ -341,6 +343,12 @@ def spec_kv_commit_tree(k_cache, v_cache, page_table, seq_lens, qo_indptr, accep
 def spec_probe_read(src, sink):
     """Linear read of the whole tensor `src`, once."""
     _check(_lib.spec_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()))
+
+
+def spec_probe_read_pages(src, pages, sink):
+    """Reads the 4 KB pages of `src` listed in `pages` (int32), each once."""
+    assert src.numel() * src.element_size() >= (int(pages.max()) + 1) * 4096 if pages.numel() else True
+    _check(_lib.spec_probe_read_pages(_ptr(src), _ptr(pages, torch.int32), pages.numel(), _ptr(sink), _stream()))
 
 
 def spec_probe_mfma(iters, constant_operands, sink):

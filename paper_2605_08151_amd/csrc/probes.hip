@@ -1,6 +1,7 @@
 // Measurement probes: what this chip delivers on the two roofs the verification kernels are priced against,
 // so that a report can put "fraction of the measured ceiling" beside "fraction of the datasheet peak".
 //   spec_probe_read   a linear device read (every byte once, 16 bytes per lane and load, many loads in flight)
+//   spec_probe_read_pages  the same bytes as whole 4 KB pages in the order of a page list (the K/V access pattern)
 //   spec_probe_mfma   a loop of independent v_mfma_f32_16x16x32_bf16 on register operands, nothing else
 // Neither is part of the verification path.
 #include "common.h"
@@ -22,6 +23,28 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict
     }
     for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
     // data-dependent, practically never true: keeps the loads alive without a store per lane
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc.x;
+}
+
+// The access pattern of paged K/V: 4 KB pages read whole, in the order of a page list (a random permutation models a
+// page pool after long serving).  One page per 256 threads and load, 8 pages in flight per workgroup.
+__global__ __launch_bounds__(256) void probe_read_pages_kernel(const u32x4* __restrict__ src, const int32_t* __restrict__ pages,
+                                                               int n_pages, uint32_t* __restrict__ sink)
+{
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const int stride = gridDim.x;
+    int i = blockIdx.x;
+    for (; i + 7 * stride < n_pages; i += 8 * stride) {
+        int pg[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) pg[k] = pages[i + k * stride];
+        u32x4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load(src + (size_t)pg[k] * 256 + threadIdx.x);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc ^= v[k];
+    }
+    for (; i < n_pages; i += stride) acc ^= __builtin_nontemporal_load(src + (size_t)pages[i] * 256 + threadIdx.x);
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = acc.x;
 }
 
@@ -112,6 +135,17 @@ extern "C" int spec_probe_read(const void* src, size_t bytes, void* sink, void* 
     const int grid = device_cu_count() * 8;
     hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src, bytes / 16, (uint32_t*)sink);
     return check_launch("spec_probe_read");
+}
+
+extern "C" int spec_probe_read_pages(const void* src, const int32_t* pages, int n_pages, void* sink, void* stream)
+{
+    using namespace specv;
+    if (!src || !pages || !sink || n_pages < 0) return fail(SPEC_EINVAL, "spec_probe_read_pages: NULL pointer or negative count");
+    if (!aligned(src, 16)) return fail(SPEC_EINVAL, "spec_probe_read_pages: 16-byte aligned buffer required");
+    if (n_pages == 0) return SPEC_OK;
+    const int grid = device_cu_count() * 8;
+    hipLaunchKernelGGL(probe_read_pages_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src, pages, n_pages, (uint32_t*)sink);
+    return check_launch("spec_probe_read_pages");
 }
 
 extern "C" double spec_probe_mfma(int iters, int constant_operands, void* sink, void* stream)

@@ -436,6 +436,270 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Large query blocks (4..8 row tiles: 49..128 query rows per kv head, e.g. 8 query heads x 9 candidate rows).
+// With that many rows the decomposition above keeps 32 accumulator registers per row tile in EVERY wave, which leaves
+// one 4-wave workgroup per CU, one K/V step in flight per wave, a cross-wave merge of all those accumulators at the end
+// of every chunk, and a prologue nobody overlaps: on chunks of ~1000 keys that overhead is as long as the streaming.
+// Here the ROWS are divided instead: wave w owns row tile w (its Q fragments in registers, its softmax state and its
+// 32 accumulator registers) and sees every key of the chunk; the K/V stages (32 keys = two pages of K and of V, 16 KB)
+// are shared by the waves through a ring of four LDS buffers filled by direct global->LDS loads, three stages ahead.
+// A row belongs to one wave, so there is no merge: a wave normalises and stores its own 16 rows.  64 KB of LDS and ~128
+// registers per wave let two workgroups share a CU, so that one's prologue and epilogue hide under the other's stream.
+// ------------------------------------------------------------------------------------------------
+constexpr int kRowsStageBytes = kWaveLds;      // 32 K rows + 32 V rows
+
+// max over the four 16-lane rows of a wave (the four key groups g of one query row l16), left in every lane, with the
+// row-swap instructions of gfx950 instead of two round trips through the LDS crossbar: v_permlane32_swap exchanges the
+// upper half of its first operand with the lower half of the second, v_permlane16_swap the odd rows of the first with
+// the even rows of the second; fed with two copies of x they leave (x_lo, x_lo) / (x_hi, x_hi), resp. rows (0,0,2,2) /
+// (1,1,3,3), whose element-wise max is the xor-32, resp. xor-16, reduction.
+__device__ inline float across_key_groups_max(float x)
+{
+    typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+    const unsigned int u = __builtin_bit_cast(unsigned int, x);
+    const u32x2_t a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    x = fmaxf(__builtin_bit_cast(float, a.x), __builtin_bit_cast(float, a.y));
+    const unsigned int v = __builtin_bit_cast(unsigned int, x);
+    const u32x2_t b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return fmaxf(__builtin_bit_cast(float, b.x), __builtin_bit_cast(float, b.y));
+}
+
+// RING: K/V stages per workgroup in LDS (RING - 1 of them in flight while one is computed)
+template <int NW, bool FINAL, int RING>
+__global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void verify_attn_rows_kernel(AttnParams p)
+{
+    constexpr int kRowsStages = RING;
+    constexpr int kThreads = NW * 64;
+    constexpr int kIssue = (16 + NW - 1) / NW;            // direct loads per wave and stage (16 in all; surplus slots repeat the last)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int kvh = blockIdx.y;
+    int split, i, ns_plan = 0, pb_plan = 0;
+    if (p.plan_items) {
+        if ((int)blockIdx.x >= p.plan_hdr[0]) return;
+        const int* it = p.plan_items + 4 * (size_t)blockIdx.x;
+        i = __builtin_amdgcn_readfirstlane(it[0]);
+        split = __builtin_amdgcn_readfirstlane(it[1]);
+        ns_plan = __builtin_amdgcn_readfirstlane(it[2]);
+        pb_plan = __builtin_amdgcn_readfirstlane(it[3]);
+    } else {
+        split = blockIdx.x;
+        i = blockIdx.z;
+    }
+    unsigned char* sRing = smem;                                         // kRowsStages x (32 K rows, 32 V rows)
+    int32_t* sPT = reinterpret_cast<int32_t*>(smem + kRowsStages * kRowsStageBytes);   // page ids of this chunk
+
+    const int r0 = p.qo_indptr[i], n = p.qo_indptr[i + 1] - r0, c = p.seq_lens[i];
+    if (!request_ok(r0, n, c, p)) {
+        if (!p.plan_items && split == 0 && kvh == 0 && tid == 0 && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_LENGTH);
+        return;
+    }
+    const int len = c + n;
+    const int ns = p.plan_items ? ns_plan : (len + p.chunk_target - 1) / p.chunk_target;
+    if (split >= ns) return;
+    const int chunk = (((len + ns - 1) / ns) + kP - 1) & ~(kP - 1);
+    const int kbeg = split * chunk;
+    const int kend = min(len, kbeg + chunk);
+    const size_t part_base = p.plan_items ? (size_t)pb_plan : (size_t)r0 * p.Hq * p.splits;
+    const size_t part_ns = p.plan_items ? (size_t)ns : (size_t)p.splits;
+    const int G = p.G, R = G * n;
+    const int32_t* pt = p.page_table + (size_t)i * p.max_pages;
+
+    // ---- page ids of the chunk -> LDS, validated once (page 0 stands in for a bad id, which is flagged) ----
+    int bad_page = 0;
+    const int npages = (kend - kbeg + kP - 1) / kP;
+    for (int pg = tid; pg < npages; pg += kThreads) {
+        int page = pt[kbeg / kP + pg];
+        if (page < 0 || page >= p.num_pages) { page = 0; bad_page = 1; }
+        sPT[pg] = page;
+    }
+    // ---- this wave's row tile: Q fragments straight into registers (row r = j*G + gq), and what the row may see ----
+    const int row = wave * 16 + l16;
+    const bool row_ok = row < R;
+    const int qj = row_ok ? row / G : 0, qg = row_ok ? row - qj * G : 0;
+    const size_t rowhead = (size_t)(r0 + qj) * p.Hq + kvh * G + qg;
+    bf16x8 qf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        u32x4 v = u32x4{0, 0, 0, 0};
+        if (row_ok) v = *reinterpret_cast<const u32x4*>(p.q + rowhead * kD + (s * 4 + g) * 8);
+        qf[s] = __builtin_bit_cast(bf16x8, v);
+    }
+    const bool tree = p.parent != nullptr;
+    int limit = row_ok ? (tree ? kend : min(c + qj + 1, kend)) : 0;      // the row sees key positions t < limit
+    // tree verification: bit a of anc is set iff candidate a is on this row's path to the root (a chain: all ones)
+    int32_t* sPar = sPT + (min(p.chunk_target, p.max_kv_len) / kP + 1);
+    // (the masks live in LDS and are read in the few stages that reach the candidates, as in the kernel above)
+    unsigned long long* sAnc = reinterpret_cast<unsigned long long*>(sPar + 64);   // [NW * 16]
+    if (tree) {
+        int bad_tree = 0;
+        if (tid < n) {
+            const int par = p.parent[r0 + tid];
+            sPar[tid] = par;
+            bad_tree = tid == 0 ? par != -1 : (par < 0 || par >= tid);
+        }
+        if (__syncthreads_or(bad_tree)) {                 // uniform: the whole workgroup leaves the request alone
+            if (tid == 0 && split == 0 && kvh == 0 && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_TREE);
+            return;
+        }
+    }
+    // chains: every candidate below the causal limit is on the path (all bits set), so one masking loop serves both
+    for (int r = tid; r < NW * 16; r += kThreads) {
+        unsigned long long m = ~0ull;
+        if (tree) {
+            m = 0ull;
+            if (r < R)
+                for (int a = r / G; a >= 0; a = sPar[a]) m |= 1ull << a;
+        }
+        sAnc[r] = m;
+    }
+    __syncthreads();                                      // page ids and masks visible
+
+    // ---- stage st of the chunk (keys kbeg + 32 st ..): its 16 direct loads are dealt to the waves, kIssue each; slots past the
+    // range read page 0 (never used), so that the wait counts are constants ----
+    const int drow = lane >> 4, dpos = lane & 15;        // direct-load role: row within a group of 4, 16-byte position
+    auto issue_stage = [&](int st) {
+        unsigned char* buf = sRing + (st & (kRowsStages - 1)) * kRowsStageBytes;
+        const int t0s = kbeg + st * 32;
+#pragma unroll
+        for (int k = 0; k < kIssue; ++k) {
+            const int q = min(wave * kIssue + k, 15);     // load q of the stage: which of K/V, which page, which 4 rows
+            const int isv = q >> 3, pg = (q >> 2) & 1, q4 = q & 3;
+            const int t0 = t0s + pg * kP;
+            const int page = (t0 < kend) ? __builtin_amdgcn_readfirstlane(sPT[(t0 - kbeg) / kP]) : 0;
+            const size_t base = ((size_t)page * p.Hkv + kvh) * (kP * kD);
+            const int row4 = q4 * 4 + drow;               // slot in the page = key & 15
+            // K: 16-byte chunk ch of a row is stored at position ch ^ (row & 15); V: 32-byte chunk c at c ^ (row & 7)
+            const int src16 = isv ? ((((dpos >> 1) ^ (row4 & 7)) << 1) | (dpos & 1)) : (dpos ^ row4);
+            const uint16_t* src = (isv ? p.v_cache : p.k_cache) + base + row4 * kD + (src16 << 3);
+            lds_dma16(src, buf + (isv * 32 + pg * 16 + q4 * 4) * kRowBytes);
+        }
+    };
+    const int nst = (kend - kbeg + 31) >> 5;
+    const bool wave_has_rows = wave * 16 < R;
+#pragma unroll
+    for (int st = 0; st < kRowsStages - 1; ++st) issue_stage(st);
+
+    f32x4 o[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = kNegBig, l_run = 0.0f;
+
+    for (int st = 0; st < nst; ++st) {
+        // this wave's loads of stage st have landed (RING - 2 younger stages may still fly); the barrier then says that every
+        // wave's have, and that every wave is done reading the buffer that stage st + RING - 1 is about to overwrite
+        constexpr int kYounger = (kRowsStages - 2) * kIssue;
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (kYounger & 15) | ((kYounger >> 4) << 14));
+        __syncthreads();
+        issue_stage(st + kRowsStages - 1);
+        const int wbase = kbeg + st * 32;
+        unsigned char* sK = sRing + (st & (kRowsStages - 1)) * kRowsStageBytes;
+        unsigned char* sV = sK + 32 * kRowBytes;
+        if (wbase + 32 > kend) {
+            // slots past the range may hold anything (even NaN patterns): P is 0 there, so V must be too
+            for (int idx = tid; idx < 32 * 16; idx += kThreads) {
+                const int vr = idx >> 4;
+                if (wbase + vr >= kend) *reinterpret_cast<u32x4*>(sV + vr * kRowBytes + (idx & 15) * 16) = u32x4{0, 0, 0, 0};
+            }
+            __syncthreads();
+        }
+        if (!wave_has_rows) continue;                     // wave-uniform: a request with fewer row tiles than the launch was built for
+        // ---- S^T = K Q^T for the two 16-key blocks ----
+        float sc[8];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + (kb * 16 + l16) * kRowBytes + (((s * 4 + g) ^ l16) << 4));
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[s], acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sc[kb * 4 + e] = acc[e] * p.scale_log2e;
+        }
+        const bool need_mask = wbase + 32 > min(c + 1, kend);
+        if (need_mask) {
+            const unsigned long long anc = sAnc[row];
+            const uint32_t anc_lo = (uint32_t)anc, anc_hi = (uint32_t)(anc >> 32);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int t = wbase + kb * 16 + g * 4 + e, rel = t - c;
+                    // a tree has at most 64 candidates (rel < 64 below the limit); a chain's mask is all ones.  Written without
+                    // short-circuit branches: plain selects on every lane
+                    const uint32_t word = (rel & 32) ? anc_hi : anc_lo;
+                    const uint32_t on_path = (word >> (rel & 31)) & 1u;
+                    const bool seen = (t < limit) & ((rel < 0) | (on_path != 0u));
+                    sc[kb * 4 + e] = seen ? sc[kb * 4 + e] : kNegBig;
+                }
+        }
+        float tmax = sc[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[e]);
+        tmax = across_key_groups_max(tmax);
+        if (__any(tmax > m_run + kMaxSlack)) {            // lazy reference maximum, as in the kernel above
+            const float m_new = fmaxf(m_run, tmax);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
+        }
+        float pr[8], psum = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            pr[e] = __builtin_amdgcn_exp2f(sc[e] - m_run);
+            if (need_mask) pr[e] = (sc[e] > 0.5f * kNegBig) ? pr[e] : 0.0f;
+            psum += pr[e];
+        }
+        l_run += psum;
+        const u32x4 pw = u32x4{pack_bf16x2(pr[0], pr[1]), pack_bf16x2(pr[2], pr[3]), pack_bf16x2(pr[4], pr[5]), pack_bf16x2(pr[6], pr[7])};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+        // ---- O^T += V^T P^T (transposing LDS read, as above) ----
+        {
+            const int vrow = 4 * g + (l16 >> 2);
+            const unsigned char* v0 = sV + vrow * kRowBytes + 8 * (l16 & 3);
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                const int off = (dt ^ (vrow & 7)) << 5;
+                const s16x4 lo = lds_read_tr(v0 + off);
+                const s16x4 hi = lds_read_tr(v0 + 16 * kRowBytes + off);
+                struct { s16x4 a, b; } pair = {lo, hi};
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pair), pf, o[dt], 0, 0, 0);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                   // nothing of this wave is still landing in LDS
+    if (bad_page && p.status_flags) atomicOr(p.status_flags, SPEC_FLAG_BAD_PAGE);
+
+    // ---- the wave's own 16 rows: lane (l16, g) holds row l16, d = 16 dt + 4 g + e ----
+    float l = l_run;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (!row_ok) return;
+    if (FINAL) {
+        const float inv = 1.0f / l;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            u32x2 packed;
+            packed.x = pack_bf16x2(o[dt][0] * inv, o[dt][1] * inv);
+            packed.y = pack_bf16x2(o[dt][2] * inv, o[dt][3] * inv);
+            *reinterpret_cast<u32x2*>(p.out + rowhead * kD + dt * 16 + g * 4) = packed;
+        }
+        if (p.lse && g == 0) p.lse[rowhead] = (m_run + log2f(l)) * 0.6931471805599453f;
+    } else {
+        const size_t slot = part_base + ((size_t)qj * p.Hq + kvh * G + qg) * part_ns + split;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4*>(p.part_o + slot * kD + dt * 16 + g * 4) = o[dt];
+        if (g == 0) { p.part_m[slot] = m_run; p.part_l[slot] = l; }
+    }
+}
+
 // Balanced work list for ragged batches (one workgroup, B <= 1024 requests).  The fixed chunk_target of the
 // host is sized for "every request as long as the bound"; when the real lengths are shorter or spread out,
 // the chip is under-filled or unbalanced.  Here the chunk length is derived from the real total instead:
@@ -703,9 +967,42 @@ static int launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t s)
     return SPEC_OK;
 }
 
+Tunable g_attn_rows{0};       // benchmark hook: row-split kernel for 4..8 row tiles: 0 = automatic (on), 1 = off
+
+Tunable g_attn_rows_ring{0};  // benchmark hook: K/V stages per workgroup of the row-split kernel, 2 or 4; 0 = automatic
+
+static size_t attn_rows_smem_bytes(int chunk_keys, int ring)
+{
+    return (size_t)ring * kRowsStageBytes + (size_t)(chunk_keys / kP + 1) * 4 + 64 * 4 + 8 + 8 * 16 * 8;
+}
+
+template <int NW, bool FINAL, int RING>
+static int launch_attn_rows_ring(const AttnParams& p, dim3 grid, hipStream_t s)
+{
+    const size_t smem = attn_rows_smem_bytes(p.chunk_target < p.max_kv_len ? p.chunk_target : p.max_kv_len, RING);
+    static LdsGrantTable granted = {};
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&verify_attn_rows_kernel<NW, FINAL, RING>), smem, granted,
+                                    "spec_verify_attn")) return rc;
+    hipLaunchKernelGGL((verify_attn_rows_kernel<NW, FINAL, RING>), grid, dim3(NW * 64), smem, s, p);
+    return SPEC_OK;
+}
+
+template <int NW, bool FINAL>
+static int launch_attn_rows(const AttnParams& p, dim3 grid, hipStream_t s)
+{
+    if (g_attn_rows_ring == 4) return launch_attn_rows_ring<NW, FINAL, 4>(p, grid, s);
+    return launch_attn_rows_ring<NW, FINAL, 2>(p, grid, s);
+}
+
+static bool attn_uses_rows_kernel(int NR) { return NR >= 4 && g_attn_rows != 1; }
+
 template <int NR>
 static int launch_attn(const AttnParams& p, dim3 grid, hipStream_t s)
 {
+    if constexpr (NR >= 4) {
+        if (attn_uses_rows_kernel(NR))
+            return p.splits == 1 ? launch_attn_rows<NR, true>(p, grid, s) : launch_attn_rows<NR, false>(p, grid, s);
+    }
     // up to 48 query rows: 8 waves (two per SIMD hide each other's loads, one K/V buffer per wave; with 3 row tiles
     // 238 registers, and 3-4 % faster than 4 waves on 32-64k contexts);
     // more rows need > 256 registers per lane: 4 waves, each double-buffering its own pages
