@@ -38,7 +38,8 @@ TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 NAMES = ("verify_attn", "lm_head", "accept", "kv_commit")
 # GPU kernel that carries a call's bytes or flops, by call and weight layout (first name found in a profile wins)
 KERNEL_OF_CALL = {
-    ("verify_attn", True): ("verify_attn_kernel",), ("verify_attn", False): ("verify_attn_kernel",),
+    ("verify_attn", True): ("verify_attn_rows_kernel", "verify_attn_kernel"),
+    ("verify_attn", False): ("verify_attn_rows_kernel", "verify_attn_kernel"),
     ("lm_head", True): ("lm_head_mfma_kernel", "lm_head_packed_kernel"),
     ("lm_head", False): ("lm_head_big2_kernel", "lm_head_big_kernel", "lm_head_skinny_kernel", "lm_head_tiled_kernel"),
     ("accept", True): ("accept_row_stats_kernel",), ("accept", False): ("accept_row_stats_kernel",),
@@ -487,7 +488,8 @@ def _algorithmic_by_kernel(cfg_name):
     b = dict(M=int((gammas + 1).sum()), ctx=ctx, gammas=gammas, temperature=torch.tensor(temp))
     alg = algorithmic(cfg, b)
     n_stoch = int((b["temperature"] > 0).sum())
-    return {"verify_attn_kernel": alg["attn_bytes"] / 1e6, "lm_head_packed_kernel": alg["lm_bytes"] / 1e6,
+    return {"verify_attn_kernel": alg["attn_bytes"] / 1e6, "verify_attn_rows_kernel": alg["attn_bytes"] / 1e6,
+            "lm_head_packed_kernel": alg["lm_bytes"] / 1e6,
             "lm_head_mfma_kernel": alg["lm_bytes"] / 1e6, "lm_head_big2_kernel": alg["lm_bytes"] / 1e6,
             "lm_head_skinny_kernel": alg["lm_bytes"] / 1e6,
             "accept_row_stats_kernel": b["M"] * cfg.V * 4 / 1e6,

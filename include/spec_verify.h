@@ -76,7 +76,11 @@ int spec_version(void);
  *   "attn_plan_waves"  work items per CU that list aims at; 0 = automatic.
  *   "attn_nr3_waves"   waves per workgroup of spec_verify_attn when a request has 33..48 query rows per kv
  *                      head: 8 (default) or 4.
- *   "lm_kernel"        kernel used by spec_lm_head: 0 = automatic (weight-streaming kernel for M <= 160,
+ *   "attn_rows"        the row-split kernel of spec_verify_attn (one 16-row tile per wave, K/V staged once per
+ *                      workgroup): 0 = automatic (49..128 query rows per kv head), 1 = never, 2 = also for
+ *                      17..48 rows.
+ *   "attn_rows_ring"   K/V stages (32 keys each) a workgroup of that kernel keeps in LDS: 2 (default) or 4.
+ *   "lm_kernel"       kernel used by spec_lm_head: 0 = automatic (weight-streaming kernel for M <= 160,
  *                      MFMA-bound kernel above), 1 = weight-streaming, 2 = MFMA-bound with direct global->LDS
  *                      loads, 3 = plain tiled, 4..7 = weight-streaming variants (wave count / register-ring
  *                      depth), 8 = MFMA-bound with register staging.

@@ -75,18 +75,17 @@ inline int ensure_dynamic_lds(const void* kernel, size_t bytes, LdsGrantTable& g
     return SPEC_OK;
 }
 
-// fp32 -> bf16, round to nearest even (inputs here are finite)
-__device__ inline uint32_t f32_to_bf16_bits(float f)
-{
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+// fp32 -> bf16, round to nearest even: the conversion instructions of gfx950 (v_cvt_pk_bf16_f32)
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+
+__device__ inline uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xFFFFu; }
 
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
 // Written as inline assembly so that the compiler does not order it against later LDS reads by draining

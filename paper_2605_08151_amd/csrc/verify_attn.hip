@@ -581,6 +581,10 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
     };
     const int nst = (kend - kbeg + 31) >> 5;
     const bool wave_has_rows = wave * 16 < R;
+    // a masked raw score: scaled it is kNegBig.  A caller's scale <= 0 makes no sense for a softmax; it is clamped to a tiny
+    // positive value so that the arithmetic stays finite
+    const float scale = fmaxf(p.scale_log2e, 1e-30f);
+    const float kMaskedRaw = kNegBig / scale < -3.0e38f ? -3.0e38f : kNegBig / scale;
 #pragma unroll
     for (int st = 0; st < kRowsStages - 1; ++st) issue_stage(st);
 
@@ -589,7 +593,8 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
     for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = kNegBig, l_run = 0.0f;
 
-    for (int st = 0; st < nst; ++st) {
+    // the stage loop is unrolled over the ring, so that a stage's buffer is a compile-time offset of every LDS read
+    auto do_stage = [&](auto slot, int st) {
         // this wave's loads of stage st have landed (RING - 2 younger stages may still fly); the barrier then says that every
         // wave's have, and that every wave is done reading the buffer that stage st + RING - 1 is about to overwrite
         constexpr int kYounger = (kRowsStages - 2) * kIssue;
@@ -597,7 +602,7 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
         __syncthreads();
         issue_stage(st + kRowsStages - 1);
         const int wbase = kbeg + st * 32;
-        unsigned char* sK = sRing + (st & (kRowsStages - 1)) * kRowsStageBytes;
+        unsigned char* sK = sRing + decltype(slot)::value * kRowsStageBytes;
         unsigned char* sV = sK + 32 * kRowBytes;
         if (wbase + 32 > kend) {
             // slots past the range may hold anything (even NaN patterns): P is 0 there, so V must be too
@@ -607,8 +612,9 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
             }
             __syncthreads();
         }
-        if (!wave_has_rows) continue;                     // wave-uniform: a request with fewer row tiles than the launch was built for
-        // ---- S^T = K Q^T for the two 16-key blocks ----
+        if (!wave_has_rows) return;                       // wave-uniform: a request with fewer row tiles than the launch was built for
+        // ---- S^T = K Q^T for the two 16-key blocks; sc holds the RAW dot products, the softmax scale (log2 domain) is
+        // folded into the one multiply-add in front of every exponential ----
         float sc[8];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
@@ -619,7 +625,7 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[s], acc, 0, 0, 0);
             }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) sc[kb * 4 + e] = acc[e] * p.scale_log2e;
+            for (int e = 0; e < 4; ++e) sc[kb * 4 + e] = acc[e];
         }
         const bool need_mask = wbase + 32 > min(c + 1, kend);
         if (need_mask) {
@@ -631,17 +637,17 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
                 for (int e = 0; e < 4; ++e) {
                     const int t = wbase + kb * 16 + g * 4 + e, rel = t - c;
                     // a tree has at most 64 candidates (rel < 64 below the limit); a chain's mask is all ones.  Written without
-                    // short-circuit branches: plain selects on every lane
+                    // short-circuit branches (plain selects on every lane): the branchy form of this test was miscompiled here
                     const uint32_t word = (rel & 32) ? anc_hi : anc_lo;
                     const uint32_t on_path = (word >> (rel & 31)) & 1u;
                     const bool seen = (t < limit) & ((rel < 0) | (on_path != 0u));
-                    sc[kb * 4 + e] = seen ? sc[kb * 4 + e] : kNegBig;
+                    sc[kb * 4 + e] = seen ? sc[kb * 4 + e] : kMaskedRaw;
                 }
         }
         float tmax = sc[0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[e]);
-        tmax = across_key_groups_max(tmax);
+        tmax = across_key_groups_max(tmax) * scale;       // scale > 0: the maximum of the scaled scores
         if (__any(tmax > m_run + kMaxSlack)) {            // lazy reference maximum, as in the kernel above
             const float m_new = fmaxf(m_run, tmax);
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -651,10 +657,13 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
             for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
         }
         float pr[8], psum = 0.0f;
+        const float neg_m = -m_run;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            pr[e] = __builtin_amdgcn_exp2f(sc[e] - m_run);
-            if (need_mask) pr[e] = (sc[e] > 0.5f * kNegBig) ? pr[e] : 0.0f;
+            // a masked score is hugely negative: its exponential is 0 unless the row has seen nothing at all
+            // (m_run == kNegBig), and such a row is masked by the comparison
+            pr[e] = __builtin_amdgcn_exp2f(fmaf(sc[e], scale, neg_m));
+            if (need_mask) pr[e] = (sc[e] > 0.5f * kMaskedRaw) ? pr[e] : 0.0f;
             psum += pr[e];
         }
         l_run += psum;
@@ -672,6 +681,14 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
                 struct { s16x4 a, b; } pair = {lo, hi};
                 o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pair), pf, o[dt], 0, 0, 0);
             }
+        }
+    };
+    for (int st0 = 0; st0 < nst; st0 += kRowsStages) {
+        do_stage(std::integral_constant<int, 0>{}, st0);
+        if (st0 + 1 < nst) do_stage(std::integral_constant<int, 1>{}, st0 + 1);
+        if constexpr (kRowsStages > 2) {
+            if (st0 + 2 < nst) do_stage(std::integral_constant<int, 2>{}, st0 + 2);
+            if (st0 + 3 < nst) do_stage(std::integral_constant<int, 3>{}, st0 + 3);
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                   // nothing of this wave is still landing in LDS
@@ -887,7 +904,7 @@ Tunable g_attn_chunk_override{0};
 // Keys per kv split.  A split costs a prologue (Q to LDS), an epilogue (cross-wave merge) and a partial
 // that the merge kernel re-reads, so requests are only split when there are too few (request, kv head)
 // units to fill the chip or when they are long enough for the length spread to unbalance it.
-static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
+static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys, int wgs_per_cu)
 {
     long target;
     const int forced = g_attn_chunk_override;
@@ -897,7 +914,7 @@ static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
         // about one workgroup per CU when every request is as long as the bound (measured best on MI355X for
         // B=8 x 64k, B=64 x 4k and B=256 x 32k lognormal alike); shorter requests simply get fewer splits
         const long units = (long)B * Hkv, cus = device_cu_count();
-        target = units * (long)max_kv_len / cus;
+        target = units * (long)max_kv_len / (cus * wgs_per_cu);
         if (target < 512) target = 512;
         if (target > 4096) target = 4096;
         if (target >= max_kv_len) target = max_kv_len;             // nobody is split: no partials, no merge kernel
@@ -908,6 +925,11 @@ static int attn_chunk_target(int B, int Hkv, int max_kv_len, int step_keys)
 
 Tunable g_attn_nr3_waves{8};  // benchmark hook: waves per workgroup when a request has 3 row tiles (8, or 4 with two K/V buffers each)
 static int attn_waves(int NR) { return NR <= 2 || (NR == 3 && g_attn_nr3_waves == 8) ? 8 : 4; }      // 8 waves need <= 256 registers per lane
+
+Tunable g_attn_rows{0};       // benchmark hook: row-split kernel: 0 = automatic (4..8 row tiles), 1 = off, 2 = also for 2..3 row tiles
+static int attn_rows_min_tiles() { const int v = g_attn_rows; return v == 1 ? 9 : (v == 2 ? 2 : 4); }
+// workgroups of one CU the fixed chunk is sized for: the row-split kernel keeps three resident, the others one
+static int attn_wgs_per_cu(int NR) { return NR >= attn_rows_min_tiles() ? 3 : 1; }
 
 // Balanced work list (verify_attn_plan_kernel): used when requests are long enough for a few microseconds of
 // planning to pay, numerous enough for their length spread to matter, and the fixed chunk would split them anyway.
@@ -967,8 +989,6 @@ static int launch_attn_one(const AttnParams& p, dim3 grid, hipStream_t s)
     return SPEC_OK;
 }
 
-Tunable g_attn_rows{0};       // benchmark hook: row-split kernel for 4..8 row tiles: 0 = automatic (on), 1 = off
-
 Tunable g_attn_rows_ring{0};  // benchmark hook: K/V stages per workgroup of the row-split kernel, 2 or 4; 0 = automatic
 
 static size_t attn_rows_smem_bytes(int chunk_keys, int ring)
@@ -994,13 +1014,14 @@ static int launch_attn_rows(const AttnParams& p, dim3 grid, hipStream_t s)
     return launch_attn_rows_ring<NW, FINAL, 2>(p, grid, s);
 }
 
-static bool attn_uses_rows_kernel(int NR) { return NR >= 4 && g_attn_rows != 1; }
+// (the row-split kernel folds the scale into its exponentials, which needs a positive, finite scale)
+static bool attn_uses_rows_kernel(int NR, float scale_log2e) { return NR >= attn_rows_min_tiles() && scale_log2e > 1e-30f && scale_log2e < 1e30f; }
 
 template <int NR>
 static int launch_attn(const AttnParams& p, dim3 grid, hipStream_t s)
 {
-    if constexpr (NR >= 4) {
-        if (attn_uses_rows_kernel(NR))
+    if constexpr (NR >= 2) {
+        if (attn_uses_rows_kernel(NR, p.scale_log2e))
             return p.splits == 1 ? launch_attn_rows<NR, true>(p, grid, s) : launch_attn_rows<NR, false>(p, grid, s);
     }
     // up to 48 query rows: 8 waves (two per SIMD hide each other's loads, one K/V buffer per wave; with 3 row tiles
@@ -1024,7 +1045,7 @@ extern "C" size_t spec_verify_attn_workspace_bytes(int B, int M, int Hq, int Hkv
     if (B <= 0 || M <= 0 || Hq <= 0 || Hkv <= 0 || max_kv_len <= 0 || Hq % Hkv != 0) return 0;
     const int G = Hq / Hkv;
     const int NR = (G * (max_q_len > 0 ? max_q_len : 1) + 15) / 16;
-    const int ct = attn_chunk_target(B, Hkv, max_kv_len, attn_waves(NR) * 32);
+    const int ct = attn_chunk_target(B, Hkv, max_kv_len, attn_waves(NR) * 32, attn_wgs_per_cu(NR));
     const size_t splits = (size_t)(max_kv_len + ct - 1) / ct;
     const size_t units = (size_t)M * Hq * splits;
     const size_t fixed = round_up(units * kD * 4, 256) + 2 * round_up(units * 4, 256);
@@ -1086,7 +1107,7 @@ extern "C" int spec_verify_attn_tree(const void* q, const void* k_cache, const v
     p.status_flags = status_flags;
     p.max_pages = max_pages_per_seq; p.num_pages = num_pages; p.Hq = Hq; p.Hkv = Hkv; p.G = G;
     p.M = M; p.max_kv_len = max_kv_len; p.max_q_len = max_q_len;
-    p.chunk_target = attn_chunk_target(B, Hkv, max_kv_len, attn_waves(NR) * 32);
+    p.chunk_target = attn_chunk_target(B, Hkv, max_kv_len, attn_waves(NR) * 32, attn_wgs_per_cu(NR));
     p.out = (uint16_t*)out; p.lse = lse;
     p.splits = (max_kv_len + p.chunk_target - 1) / p.chunk_target;
     p.scale_log2e = scale * 1.4426950408889634f;
