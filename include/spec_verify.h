@@ -80,6 +80,10 @@ int spec_version(void);
  *                      workgroup): 0 = automatic (49..128 query rows per kv head), 1 = never, 2 = also for
  *                      17..48 rows.
  *   "attn_rows_ring"   K/V stages (32 keys each) a workgroup of that kernel keeps in LDS: 2 (default) or 4.
+ *   "accept_filter"    how spec_accept normalises the rows of sampled requests: 0 = automatic and 1 = fp32 sums over
+ *                      every row, an interval test, and fp64 sums only on the row a bonus token is drawn from and on
+ *                      rows whose test the interval leaves open; 2 = fp64 sums over every row; 3 = as 1 with an
+ *                      interval so wide that most tests take the fp64 path (a test hook).  Same integers in all.
  *   "lm_kernel"       kernel used by spec_lm_head: 0 = automatic (weight-streaming kernel for M <= 160,
  *                      MFMA-bound kernel above), 1 = weight-streaming, 2 = MFMA-bound with direct global->LDS
  *                      loads, 3 = plain tiled, 4..7 = weight-streaming variants (wave count / register-ring
@@ -227,6 +231,10 @@ int spec_lm_head_packed_stats(const void* hidden, const void* Wp, float* logits,
  *   bonus draw at j* (or gamma_i + 1 when nothing is rejected); the first
  *   output word's top 24 bits give u in [0, 1).  Probabilities, sums and
  *   products are formed in fp64 and rounded to fp32 before they are compared.
+ *   (A test whose outcome is the same at both ends of the error interval of an
+ *   fp32 estimate of the normaliser is settled from that estimate; any other,
+ *   and every bonus draw, uses the fp64 sum.  The integers returned are those of
+ *   the fp64 definition; "accept_filter" of spec_set_tuning turns the estimate off.)
  *
  *   logits [M, V] fp32; tokens [M] int32 (row 0 of a request = its last
  *   committed token, unused here); draft_probs [M - B, V] fp32 or NULL;

@@ -2,15 +2,23 @@
 // Selection": after the verification pass the target performs rejection sampling and identifies the
 // rollback set; Appendix "Target side": the target computes the accepted length L).
 //
-// Four kernels, all HBM-bound scans or tiny per-request work:
+// Kernels, all HBM-bound scans or tiny per-request work:
 //   1. row_stats      grid (segments, rows): per 4096-logit segment the max, the lowest argmax, a NaN
-//                     flag and, for sampled requests, sum exp((l - max_seg)/T) in fp64.
-//   2. decide         one wave per request: merges the segments of each row, then lane 0 walks the
-//                     drafts (prefix match, or u*q < p with a Philox uniform) and emits the accepted
-//                     drafts; greedy requests are finished here.
+//                     flag and, for sampled requests, sum exp((l - max_seg)/T): in fp32 (an estimate good to
+//                     2^-16, the default) or in fp64.
+//   2. decide         one workgroup per request, one wave per row: merges the segments of each row; then every
+//                     draft's test is evaluated at once (prefix match, or u*q < p with a Philox uniform) and the
+//                     accepted length is the position of the first failure.  With fp32 sums the test is taken
+//                     against both ends of the interval p must lie in; where they disagree the row is summed
+//                     again in fp64 by the workgroup, so the outcome is always that of the fp64 definition.
+//                     Greedy requests are finished here.
+//   3a. bonus_z       (fp32 sums only) grid (segments, requests): fp64 segment sums of exp((l - m)/T) on the one
+//                     row per sampled request that the bonus token is drawn from.
 //   3. residual_sums  grid (segments, requests): for sampled requests, fp64 segment sums of the
-//                     residual max(0, p - q) (and of p) on the one row the bonus is drawn from.
+//                     residual max(0, p - q) (and of p) on that row.
 //   4. pick           one workgroup per request: inverse CDF over segment sums, then inside the segment.
+// The fp64 exponential over all M rows made row_stats ALU-bound (103 us against 59 us for the same scan without it,
+// B = 64, M = 576, V = 151936); only one row per request needs its normaliser to the last bit.
 // Probabilities are formed in fp64 and rounded to fp32 before they are compared or subtracted, so the
 // integer outputs do not depend on summation order beyond ~1e-16 relative.
 #include "common.h"
@@ -22,6 +30,10 @@ constexpr int kThreads = 256;
 constexpr int kPerThread = kSeg / kThreads;   // 16
 constexpr int kMaxRows = 64;        // gamma_max + 1 <= 64
 constexpr int kPickLds = 512;       // segment sums staged in LDS by the pick kernel (V <= 2M entries)
+
+// benchmark / test hook: 0 = automatic (on), 1 = on, 2 = off (fp64 sums over every row), 3 = on with an interval so wide
+// that most tests are settled by the exact fallback
+Tunable g_accept_filter{0};
 
 struct AcceptWorkspace {
     float* seg_max;      // [M, nseg]
@@ -37,6 +49,7 @@ struct AcceptWorkspace {
     int32_t* job_row;    // [B]  logits row the bonus is drawn from, -1 = nothing to draw
     int32_t* job_qrow;   // [B]  draft_probs row subtracted, -1 = none
     int32_t* job_onehot; // [B]  token of a one-hot drafter, -1 = none
+    double* job_zseg;    // [B, nseg]  fp64 segment sums of exp((l - m)/T) on the bonus row (when the bulk sums are fp32)
 };
 
 static size_t carve(AcceptWorkspace* w, char* base, int B, int M, int nseg)
@@ -47,6 +60,7 @@ static size_t carve(AcceptWorkspace* w, char* base, int B, int M, int nseg)
     w->seg_z = (double*)take(rs * 8);
     w->res_sum = (double*)take(bs * 8);
     w->p_sum = (double*)take(bs * 8);
+    w->job_zseg = (double*)take(bs * 8);
     w->job_m = (double*)take((size_t)B * 8);
     w->job_z = (double*)take((size_t)B * 8);
     w->seg_max = (float*)take(rs * 4);
@@ -178,7 +192,7 @@ constexpr int kSegPerWg = 1;        // consecutive segments one workgroup handle
 __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
     const float* __restrict__ logits, const float* __restrict__ temperature,
     const int32_t* __restrict__ qo_indptr, int B, int V, int nseg, bool vec,
-    AcceptWorkspace w, int32_t* __restrict__ stats, bool greedy_rows_covered)
+    AcceptWorkspace w, int32_t* __restrict__ stats, bool greedy_rows_covered, bool fp32_sums)
 {
     __shared__ float s_m[kSegPerWg][kThreads / 64];
     __shared__ int s_a[kSegPerWg][kThreads / 64];
@@ -232,9 +246,22 @@ __global__ __launch_bounds__(kThreads) void accept_row_stats_kernel(
         for (int q = 0; q < kSegPerWg; ++q) {
             double z = 0.0;
             if (!bb[q] && bm[q] > -INFINITY && bm[q] < INFINITY) {
-                const double dm = (double)bm[q];
+                if (fp32_sums) {
+                    // An estimate for the interval test of the decision kernel, which asks for it within 2^-14 of the
+                    // fp64 sum.  Per term: the exponent (l - max) * log2(e)/T carries three fp32 roundings (<= 1.8e-7
+                    // relative, i.e. <= 1.24e-7 |a| relative in 2^a) and the hardware exponential one ulp, together
+                    // <= 8.1e-6 for |a| <= 64; terms beyond add < 4096 * 2^-64 to a sum >= 1; sixteen fp32 additions
+                    // per lane add <= 1e-6.  The partial sums are then carried in fp64.  Total < 2^-16.
+                    const float c = (float)(1.4426950408889634 * inv_t), fm = bm[q];
+                    float zf = 0.0f;
 #pragma unroll
-                for (int k = 0; k < kPerThread; ++k) z += exp_bulk(((double)x[q][k] - dm) * inv_t, s_tbl);
+                    for (int k = 0; k < kPerThread; ++k) zf += __builtin_amdgcn_exp2f((x[q][k] - fm) * c);
+                    z = (double)zf;
+                } else {
+                    const double dm = (double)bm[q];
+#pragma unroll
+                    for (int k = 0; k < kPerThread; ++k) z += exp_bulk(((double)x[q][k] - dm) * inv_t, s_tbl);
+                }
             }
             z = wave_sum(z);
             if (lane == 0) s_z[q][wave] = z;
@@ -261,20 +288,22 @@ __global__ void accept_reset_stats_kernel(int32_t* __restrict__ stats, int B)
 }
 
 // ---- 2. per-request decision -----------------------------------------------------------------
-__global__ __launch_bounds__(256) void accept_decide_kernel(
+constexpr int kDecideThreads = 1024;   // 16 waves: the rows of a request (gamma + 1 <= 16 in practice) are merged side by side
+
+__global__ __launch_bounds__(kDecideThreads) void accept_decide_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ tokens, const float* __restrict__ draft_probs,
     const float* __restrict__ temperature, const uint64_t* __restrict__ seeds, uint32_t round,
     const int32_t* __restrict__ qo_indptr, int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens,
     uint8_t* __restrict__ rollback, int32_t* __restrict__ stats, int M, int V, int nseg, int gamma_max,
     AcceptWorkspace w, int32_t* __restrict__ status_flags,
-    const float* __restrict__ blk_max, const int32_t* __restrict__ blk_arg, int nblk)
+    const float* __restrict__ blk_max, const int32_t* __restrict__ blk_arg, int nblk, float band)
 {
     __shared__ double s_m[kMaxRows], s_z[kMaxRows];
     __shared__ int s_arg[kMaxRows], s_bad[kMaxRows];
     const int i = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, tid = threadIdx.x;
     const int r0 = qo_indptr[i], gamma = qo_indptr[i + 1] - r0 - 1;
     int32_t* emit = out_tokens + (size_t)i * (gamma_max + 1);
-    for (int j = tid; j <= gamma_max; j += 256) emit[j] = -1;
+    for (int j = tid; j <= gamma_max; j += kDecideThreads) emit[j] = -1;
     if (tid == 0) { w.job_row[i] = -1; accept_len[i] = 0; if (rollback) rollback[i] = 0; }
     if (gamma < 0 || gamma > gamma_max || r0 < 0 || r0 + gamma + 1 > M) {
         if (tid == 0 && status_flags) atomicOr(status_flags, SPEC_FLAG_BAD_LENGTH);
@@ -283,7 +312,7 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
     const float T = temperature[i];
     const double Td = (double)T;
     const bool from_blocks = nblk > 0 && T == 0.0f;        // greedy: maxima the LM head left per vocabulary block
-    for (int j = wave; j <= gamma; j += 4) {               // rows are merged by the four waves in parallel
+    for (int j = wave; j <= gamma; j += kDecideThreads / 64) {   // one wave per row
         const size_t base = (size_t)(r0 + j) * nseg;
         float m = -INFINITY;
         int arg = 0x7FFFFFFF, bad = 0;
@@ -312,11 +341,15 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
             bad |= w.seg_bad[base + s];
             if (sm > m || (sm == m && sa < arg)) { m = sm; arg = sa; }
         }
+        // (the first 64 segment sums are requested together with the maxima: one memory round trip for V <= 262144)
+        const double z_first = (T > 0.0f && lane < nseg) ? w.seg_z[base + lane] : 0.0;
+        const float m_first = lane < nseg ? w.seg_max[base + lane] : -INFINITY;
         wave_max_arg(m, arg);
         bad = __any(bad) || !(m > -INFINITY && m < INFINITY);
         double z = 0.0;
         if (T > 0.0f && !bad) {
-            for (int s = lane; s < nseg; s += 64) {
+            if (m_first > -INFINITY) z = z_first * exp(((double)m_first - (double)m) / Td);
+            for (int s = lane + 64; s < nseg; s += 64) {
                 const float sm = w.seg_max[base + s];
                 if (sm > -INFINITY) z += w.seg_z[base + s] * exp(((double)sm - (double)m) / Td);
             }
@@ -336,61 +369,102 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
         s_qd[tid] = (ok && T > 0.0f && draft_probs) ? draft_probs[(size_t)(r0 - i + tid - 1) * V + d] : 1.0f;
     }
     __syncthreads();
-    if (tid != 0) return;
 
+    // Every wave evaluates the same tests on the same LDS data (so that the branches below are uniform for the whole
+    // workgroup); wave 0 alone writes.  Lane j looks at row j (its logits usable?) and at draft j (1 <= j <= gamma <= 63):
+    // every draft's test is evaluated at once, and the accepted length is the number of drafts before the first that fails.
+    const bool w0 = wave == 0;
+    const bool has_draft = lane >= 1 && lane <= gamma;
+    const int d = has_draft ? s_tok[lane] : 0;
     int flags = 0;
     bool valid = (T >= 0.0f);
     if (T > 0.0f && seeds == nullptr) { valid = false; flags |= SPEC_FLAG_NO_SEED; }
-    for (int j = 0; j <= gamma; ++j) if (s_bad[j]) { valid = false; flags |= SPEC_FLAG_BAD_LOGITS; }
-    for (int j = 1; j <= gamma; ++j) {
-        const int d = s_tok[j];
-        if (d < 0 || d >= V) { valid = false; flags |= SPEC_FLAG_BAD_TOKEN; }
-    }
+    if (__any(lane <= gamma && s_bad[lane])) { valid = false; flags |= SPEC_FLAG_BAD_LOGITS; }
+    if (__any(has_draft && (d < 0 || d >= V))) { valid = false; flags |= SPEC_FLAG_BAD_TOKEN; }
     if (!(T >= 0.0f)) flags |= SPEC_FLAG_BAD_LOGITS;
-    int a = 0;
     if (!valid) {
-        if (rollback) rollback[i] = (uint8_t)(gamma > 0);
-        if (stats) { if (gamma > 0) atomicAdd(stats + 0, 1); }
-        if (status_flags && flags) atomicOr(status_flags, flags);
+        if (tid == 0) {
+            if (rollback) rollback[i] = (uint8_t)(gamma > 0);
+            if (stats) { if (gamma > 0) atomicAdd(stats + 0, 1); }
+            if (status_flags && flags) atomicOr(status_flags, flags);
+        }
         return;
     }
+    int a, bonus = -1;
     if (T == 0.0f) {
-        while (a < gamma && s_tok[a + 1] == s_arg[a]) ++a;
-        emit[a] = s_arg[a];
+        const unsigned long long miss = __ballot(has_draft && d != s_arg[lane - 1]);
+        a = miss ? __ffsll((long long)miss) - 2 : gamma;  // bit j is the first mismatch: drafts 1..j-1 stand
+        bonus = s_arg[a];
     } else {
+        // Draft j stands iff fl32(u q) < fl32(e / Z), e = exp((l - m)/T), Z the fp64 sum over the row.  s_z holds Z itself
+        // (band == 0) or an fp32-summed estimate within a relative `band` of it: the test is then taken against both ends
+        // of the interval that fl32(e / Z) must lie in, and only where the two disagree is the row summed again in fp64,
+        // by the whole workgroup.  The outcome is that of the exact test in every case.
+        enum { kPass = 0, kFail = 1, kOpen = 2 };
         const uint64_t seed = seeds[i];
-        int rejected_at = 0;
-        for (int j = 1; j <= gamma; ++j) {
-            const double l = (double)s_logit[j];
-            const float p = (float)(exp((l - s_m[j - 1]) / Td) / s_z[j - 1]);
-            const float qd = s_qd[j];
-            const float u = philox_uniform(seed, round, (uint32_t)j, 0u);
-            if ((float)((double)u * (double)qd) < p) ++a;
-            else { rejected_at = j; break; }
+        int state = kPass;
+        double e = 0.0;
+        float x = 0.0f;
+        if (has_draft) {
+            e = exp(((double)s_logit[lane] - s_m[lane - 1]) / Td);
+            const double zj = s_z[lane - 1];
+            const float u = philox_uniform(seed, round, (uint32_t)lane, 0u);
+            x = (float)((double)u * (double)s_qd[lane]);
+            const float p_lo = (float)(e / (zj * (1.0 + (double)band))), p_hi = (float)(e / (zj * (1.0 - (double)band)));
+            state = x < p_lo ? kPass : (x < p_hi ? kOpen : kFail);
         }
-        if (rejected_at) {
-            w.job_row[i] = r0 + rejected_at - 1;
-            w.job_qrow[i] = draft_probs ? (r0 - i + rejected_at - 1) : -1;
-            w.job_onehot[i] = draft_probs ? -1 : s_tok[rejected_at];
-            w.job_u[i] = philox_uniform(seed, round, (uint32_t)rejected_at, 1u);
-            w.job_m[i] = s_m[rejected_at - 1];
-            w.job_z[i] = s_z[rejected_at - 1];
-        } else {
-            w.job_row[i] = r0 + gamma;
-            w.job_qrow[i] = -1;
-            w.job_onehot[i] = -1;
-            w.job_u[i] = philox_uniform(seed, round, (uint32_t)(gamma + 1), 1u);
-            w.job_m[i] = s_m[gamma];
-            w.job_z[i] = s_z[gamma];
+        __shared__ int s_need;
+        __shared__ double s_exact, s_part[kDecideThreads / 64], s_tbl[64];
+        bool table_loaded = false;
+        for (;;) {
+            const unsigned long long fails = __ballot(state == kFail), opens = __ballot(state == kOpen);
+            const unsigned long long before_fail = fails ? ((fails & (0ull - fails)) - 1ull) : ~0ull;
+            const unsigned long long undecided = opens & before_fail;     // open tests that the outcome depends on
+            const int need = undecided ? __ffsll((long long)undecided) - 2 : -1;   // bit j: draft j is tested on row j-1
+            if (need < 0) break;                          // (the same in every wave: same data, same arithmetic)
+            if (!table_loaded) { load_exp_table(s_tbl, tid); table_loaded = true; __syncthreads(); }
+            const float* lrow = logits + (size_t)(r0 + need) * V;
+            const double mrow = s_m[need], inv_t = 1.0 / Td;
+            double z = 0.0;
+            for (int v = tid; v < V; v += kDecideThreads) z += exp_bulk(((double)lrow[v] - mrow) * inv_t, s_tbl);
+            z = wave_sum(z);
+            if (lane == 0) s_part[wave] = z;
+            __syncthreads();
+            if (tid == 0) {
+                double t = 0.0;
+                for (int k = 0; k < kDecideThreads / 64; ++k) t += s_part[k];
+                s_exact = t; s_z[need] = t;
+            }
+            __syncthreads();
+            if (lane == need + 1) state = x < (float)(e / s_exact) ? kPass : kFail;
+            __syncthreads();                              // s_part and s_exact are free again
         }
-        w.job_t[i] = T;
+        const unsigned long long fail_mask = __ballot(state == kFail);
+        const int rejected_at = fail_mask ? __ffsll((long long)fail_mask) - 1 : 0;
+        a = rejected_at ? rejected_at - 1 : gamma;
+        if (tid == 0) {
+            // the bonus is drawn on the row that rejected (from the residual) or on the last row (from the target itself)
+            const int jr = rejected_at ? rejected_at - 1 : gamma;
+            w.job_row[i] = r0 + jr;
+            w.job_qrow[i] = (rejected_at && draft_probs) ? (r0 - i + jr) : -1;
+            w.job_onehot[i] = (rejected_at && !draft_probs) ? s_tok[rejected_at] : -1;
+            w.job_u[i] = philox_uniform(seed, round, (uint32_t)(rejected_at ? rejected_at : gamma + 1), 1u);
+            w.job_m[i] = s_m[jr];
+            w.job_z[i] = s_z[jr];                         // (an estimate when band > 0: the draw then sums the row itself)
+            w.job_t[i] = T;
+        }
     }
-    for (int j = 0; j < a; ++j) emit[j] = s_tok[j + 1];
-    accept_len[i] = a;
-    if (rollback) rollback[i] = (uint8_t)(a < gamma);
-    if (stats) {
-        if (a < gamma) atomicAdd(stats + 0, 1);
-        atomicAdd(stats + 1, a + 1);
+    if (!w0) return;
+    // lane j writes slot j: the accepted drafts, then (greedy) the bonus; sampled requests get theirs from the draw
+    if (lane < a) emit[lane] = s_tok[lane + 1];
+    else if (lane == a && bonus >= 0) emit[lane] = bonus;
+    if (lane == 0) {
+        accept_len[i] = a;
+        if (rollback) rollback[i] = (uint8_t)(a < gamma);
+        if (stats) {
+            if (a < gamma) atomicAdd(stats + 0, 1);
+            atomicAdd(stats + 1, a + 1);
+        }
     }
 }
 
@@ -467,72 +541,158 @@ __global__ __launch_bounds__(256) void accept_decide_tree_kernel(
 }
 
 // residual weight of vocabulary entry v on the job's row: max(0, p(v) - q(v)) in fp32, and p(v)
-__device__ inline void residual_of(float l, float qv, double m, double inv_t, double z, const double* s_tbl, float& p, float& rho)
+// e / z with z >= 1 and 0 < e <= 2.03 (no scaling needed): rz is the correctly rounded 1 / z, the product is within an
+// ulp of the quotient, and one exact remainder (a fused multiply-add) corrects it to the correctly rounded quotient
+// (Markstein's theorem), i.e. to the value the division instruction sequence returns, in 3 instead of ~15 operations.
+__device__ inline double quotient_by(double e, double z, double rz)
 {
-    p = (float)(exp_bulk(((double)l - m) * inv_t, s_tbl) / z);
+    const double q0 = e * rz;
+    return fma(fma(-q0, z, e), rz, q0);
+}
+
+__device__ inline void residual_of(float l, float qv, double m, double inv_t, double z, double rz, const double* s_tbl, float& p, float& rho)
+{
+    p = (float)quotient_by(exp_bulk(((double)l - m) * inv_t, s_tbl), z, rz);
     const float diff = p - qv;
     rho = diff > 0.0f ? diff : 0.0f;
+}
+
+// What a workgroup needs to know about the row a request's bonus token is drawn from.  Every field is fetched before
+// the first is looked at (one memory round trip); for a request that draws nothing (row < 0) the rest is stale, unused.
+struct BonusJob {
+    int row, qrow, onehot;
+    double m, inv_t;
+    float u;
+};
+
+__device__ inline BonusJob load_job(const AcceptWorkspace& w, int i)
+{
+    BonusJob j;
+    j.row = w.job_row[i]; j.qrow = w.job_qrow[i]; j.onehot = w.job_onehot[i];
+    j.m = w.job_m[i]; j.u = w.job_u[i];
+    j.inv_t = 1.0 / (double)w.job_t[i];
+    return j;
+}
+
+// Z of the bonus row: either what the decision kernel left (sums_exact: every row's Z was summed in fp64), or the sum
+// of the per-segment fp64 sums of accept_bonus_z_kernel.  Lane s of wave 0 takes segments s, s + 64, ...; the butterfly
+// that follows adds in a fixed order, so every workgroup of a request arrives at the same bits.  Returned through LDS
+// (s_z), visible after the caller's next barrier.
+__device__ inline void stage_bonus_z(const AcceptWorkspace& w, int i, int nseg, bool z_from_segments, double* s_z, int tid)
+{
+    if (tid >= 64) return;
+    double z = 0.0;
+    if (z_from_segments) {
+        for (int s = tid; s < nseg; s += 64) z += w.job_zseg[(size_t)i * nseg + s];
+        z = wave_sum(z);
+    } else {
+        z = w.job_z[i];
+    }
+    if (tid == 0) *s_z = z;
+}
+
+// ---- 3a. exact Z of the one row per request that the bonus is drawn from --------------------------
+// (only when the bulk sums were taken in fp32, see accept_row_stats_kernel)
+constexpr int kJobSegs = 1;         // consecutive segments per workgroup of the two bonus-row kernels (2 measured no faster:
+                                    // their time is launch + two memory round trips + the fp64 exponentials, all in one round)
+
+__global__ __launch_bounds__(kThreads) void accept_bonus_z_kernel(const float* __restrict__ logits, int V, int nseg, bool vec,
+                                                                  AcceptWorkspace w)
+{
+    __shared__ double s_part[kJobSegs][kThreads / 64];
+    __shared__ double s_tbl[64];
+    const int seg0 = blockIdx.x * kJobSegs, i = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const BonusJob job = load_job(w, i);
+    if (job.row < 0) return;
+    load_exp_table(s_tbl, tid);
+    float x[kJobSegs][kPerThread];
+#pragma unroll
+    for (int q = 0; q < kJobSegs; ++q) {
+        const int v0 = (seg0 + q) * kSeg;
+        load_strided(logits + (size_t)job.row * V, min(v0, V), min(V, v0 + kSeg), vec, tid, x[q]);   // past the row: all -inf
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kJobSegs; ++q) {
+        double z = 0.0;
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) z += exp_bulk(((double)x[q][k] - job.m) * job.inv_t, s_tbl);   // -inf slots add ~1e-304
+        z = wave_sum(z);
+        if (lane == 0) s_part[q][wave] = z;
+    }
+    __syncthreads();
+    if (tid < kJobSegs && seg0 + tid < nseg) {
+        double t = 0.0;
+        for (int k = 0; k < kThreads / 64; ++k) t += s_part[tid][k];
+        w.job_zseg[(size_t)i * nseg + seg0 + tid] = t;
+    }
 }
 
 // ---- 3. segment sums of the residual ---------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void accept_residual_sums_kernel(
     const float* __restrict__ logits, const float* __restrict__ draft_probs, int V, int nseg, bool vec,
-    AcceptWorkspace w)
+    bool z_from_segments, AcceptWorkspace w)
 {
-    __shared__ double s_r[kThreads / 64], s_p[kThreads / 64];
+    __shared__ double s_r[kJobSegs][kThreads / 64], s_p[kJobSegs][kThreads / 64];
     __shared__ double s_tbl[64];
-    const int seg = blockIdx.x, i = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int row = w.job_row[i];
-    if (row < 0) return;
+    __shared__ double s_z;
+    const int seg0 = blockIdx.x * kJobSegs, i = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const BonusJob job = load_job(w, i);
+    stage_bonus_z(w, i, nseg, z_from_segments, &s_z, tid);
+    if (job.row < 0) return;
     load_exp_table(s_tbl, tid);
-    __syncthreads();
-    const int qrow = w.job_qrow[i], onehot = w.job_onehot[i];
-    const double m = w.job_m[i], z = w.job_z[i], inv_t = 1.0 / (double)w.job_t[i];
-    const int v0 = seg * kSeg, vend = min(V, v0 + kSeg);
-    float x[kPerThread], qv[kPerThread];
-    load_strided(logits + (size_t)row * V, v0, vend, vec, tid, x);
-    if (qrow >= 0) {
-        load_strided(draft_probs + (size_t)qrow * V, v0, vend, vec, tid, qv);
+    float x[kJobSegs][kPerThread], qv[kJobSegs][kPerThread];
+#pragma unroll
+    for (int q = 0; q < kJobSegs; ++q) {
+        const int v0 = min((seg0 + q) * kSeg, V), vend = min(V, v0 + kSeg);
+        load_strided(logits + (size_t)job.row * V, v0, vend, vec, tid, x[q]);
+        if (job.qrow >= 0) load_strided(draft_probs + (size_t)job.qrow * V, v0, vend, vec, tid, qv[q]);
     }
-    double rs = 0.0, ps = 0.0;
-#pragma unroll
-    for (int it = 0; it < kPerThread / 4; ++it)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int v = v0 + (it * kThreads + tid) * 4 + k;
-            if (v < vend) {
-                const float q = qrow >= 0 ? qv[it * 4 + k] : (v == onehot ? 1.0f : 0.0f);
-                float p, rho;
-                residual_of(x[it * 4 + k], q, m, inv_t, z, s_tbl, p, rho);
-                rs += (double)rho;
-                ps += (double)p;
-            }
-        }
-    rs = wave_sum(rs);
-    ps = wave_sum(ps);
-    if (lane == 0) { s_r[wave] = rs; s_p[wave] = ps; }
     __syncthreads();
-    if (tid == 0) {
+    const double z = s_z, rz = 1.0 / z;
+#pragma unroll
+    for (int q = 0; q < kJobSegs; ++q) {
+        const int v0 = (seg0 + q) * kSeg, vend = min(V, v0 + kSeg);
+        double rs = 0.0, ps = 0.0;
+#pragma unroll
+        for (int it = 0; it < kPerThread / 4; ++it)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int v = v0 + (it * kThreads + tid) * 4 + k;
+                if (v < vend) {
+                    const float qd = job.qrow >= 0 ? qv[q][it * 4 + k] : (v == job.onehot ? 1.0f : 0.0f);
+                    float p, rho;
+                    residual_of(x[q][it * 4 + k], qd, job.m, job.inv_t, z, rz, s_tbl, p, rho);
+                    rs += (double)rho;
+                    ps += (double)p;
+                }
+            }
+        rs = wave_sum(rs);
+        ps = wave_sum(ps);
+        if (lane == 0) { s_r[q][wave] = rs; s_p[q][wave] = ps; }
+    }
+    __syncthreads();
+    if (tid < kJobSegs && seg0 + tid < nseg) {
         double r = 0.0, p = 0.0;
-        for (int k = 0; k < kThreads / 64; ++k) { r += s_r[k]; p += s_p[k]; }
-        w.res_sum[(size_t)i * nseg + seg] = r;
-        w.p_sum[(size_t)i * nseg + seg] = p;
+        for (int k = 0; k < kThreads / 64; ++k) { r += s_r[tid][k]; p += s_p[tid][k]; }
+        w.res_sum[(size_t)i * nseg + seg0 + tid] = r;
+        w.p_sum[(size_t)i * nseg + seg0 + tid] = p;
     }
 }
 
 // ---- 4. inverse CDF ----------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void accept_pick_kernel(
     const float* __restrict__ logits, const float* __restrict__ draft_probs, const int32_t* __restrict__ accept_len,
-    int32_t* __restrict__ out_tokens, int V, int nseg, int gamma_max, AcceptWorkspace w)
+    int32_t* __restrict__ out_tokens, int V, int nseg, int gamma_max, bool vec, bool z_from_segments, AcceptWorkspace w)
 {
     __shared__ int s_seg, s_use_p, s_best, s_last;
-    __shared__ double s_before, s_target, s_wave[kThreads / 64];
+    __shared__ double s_before, s_target, s_wave[kThreads / 64], s_z;
     __shared__ double s_tbl[64];
     const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int row = w.job_row[i];
-    if (row < 0) return;
-    load_exp_table(s_tbl, tid);                           // visible after the barrier below
-    // the segment sums are walked by one thread: up to kPickLds of them come to LDS in one round trip first
+    // everything that depends on the request alone is requested at once: one memory round trip, not five
+    const BonusJob job = load_job(w, i);
+    const int slot = accept_len[i];
+    // the segment sums are walked by one thread: up to kPickLds of them come to LDS first
     __shared__ double s_rs[kPickLds], s_ps[kPickLds];
     const bool staged = nseg <= kPickLds;
     if (staged) {
@@ -540,42 +700,85 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(
             s_rs[s] = w.res_sum[(size_t)i * nseg + s];
             s_ps[s] = w.p_sum[(size_t)i * nseg + s];
         }
-        __syncthreads();
     }
-    if (tid == 0) {
-        const double* rs = staged ? s_rs : w.res_sum + (size_t)i * nseg;
-        double total = 0.0;
-        for (int s = 0; s < nseg; ++s) total += rs[s];
-        int use_p = 0;
-        if (!(total > 0.0)) {                  // p == q numerically: draw from p itself
-            use_p = 1;
-            rs = staged ? s_ps : w.p_sum + (size_t)i * nseg;
-            total = 0.0;
-            for (int s = 0; s < nseg; ++s) total += rs[s];
-        }
-        const double target = (double)w.job_u[i] * total;
-        double run = 0.0;
+    stage_bonus_z(w, i, nseg, z_from_segments, &s_z, tid);
+    if (job.row < 0) return;
+    load_exp_table(s_tbl, tid);
+    __syncthreads();
+    if (wave == 0) {
+        // Wave 0 walks the segment sums 64 at a time: totals, then an inclusive scan against u * total.  (One thread
+        // doing this serially spends a load latency per segment.)  The sums are non-negative, so the first lane whose
+        // running sum exceeds the target marks the segment.
+        auto seg_sum = [&](int s, int from_p) -> double {
+            if (staged) return from_p ? s_ps[s] : s_rs[s];
+            return from_p ? w.p_sum[(size_t)i * nseg + s] : w.res_sum[(size_t)i * nseg + s];
+        };
+        double tr = 0.0, tp = 0.0;
+        for (int s = lane; s < nseg; s += 64) { tr += seg_sum(s, 0); tp += seg_sum(s, 1); }
+        tr = wave_sum(tr);
+        tp = wave_sum(tp);
+        const int use_p = !(tr > 0.0);                    // p == q numerically: draw from p itself
+        const double target = (double)job.u * (use_p ? tp : tr);
+        double carry = 0.0, before = 0.0;
         int found = -1, last_pos = 0;
-        for (int s = 0; s < nseg; ++s) {
-            if (rs[s] > 0.0) last_pos = s;
-            if (run + rs[s] > target) { found = s; break; }
-            run += rs[s];
+        for (int base = 0; base < nseg && found < 0; base += 64) {
+            const int s = base + lane;
+            const double v = s < nseg ? seg_sum(s, use_p) : 0.0;
+            double incl = v;
+#pragma unroll
+            for (int dd = 1; dd < 64; dd <<= 1) {
+                const double up = __shfl_up(incl, dd, 64);
+                if (lane >= dd) incl += up;
+            }
+            const unsigned long long over = __ballot(s < nseg && carry + incl > target);
+            const unsigned long long pos = __ballot(s < nseg && v > 0.0);
+            if (over) {
+                const int l = __ffsll((long long)over) - 1;
+                found = base + l;
+                before = carry + __shfl(incl - v, l, 64);
+                const unsigned long long pos_upto = pos & ((2ull << l) - 1ull);
+                if (pos_upto) last_pos = base + 63 - __clzll((long long)pos_upto);
+            } else {
+                if (pos) last_pos = base + 63 - __clzll((long long)pos);
+                carry += __shfl(incl, 63, 64);
+            }
         }
-        if (found < 0) {                       // rounding ran the CDF out: last segment with weight
+        if (found < 0) {                                  // rounding ran the CDF out: last segment with weight
             found = last_pos;
-            run = 0.0;
-            for (int s = 0; s < found; ++s) run += rs[s];
+            double b = 0.0;
+            for (int s = lane; s < found; s += 64) b += seg_sum(s, use_p);
+            before = wave_sum(b);
         }
-        s_seg = found; s_use_p = use_p; s_before = run; s_target = target;
-        s_best = 0x7FFFFFFF; s_last = -1;
+        if (lane == 0) {
+            s_seg = found; s_use_p = use_p; s_before = before; s_target = target;
+            s_best = 0x7FFFFFFF; s_last = -1;
+        }
     }
     __syncthreads();
     const int seg = s_seg, use_p = s_use_p;
-    const int qrow = use_p ? -1 : w.job_qrow[i], onehot = use_p ? -1 : w.job_onehot[i];
-    const double m = w.job_m[i], z = w.job_z[i], inv_t = 1.0 / (double)w.job_t[i];
+    const int qrow = use_p ? -1 : job.qrow, onehot = use_p ? -1 : job.onehot;
+    const double z = s_z, rz = 1.0 / z;
     const int v0 = seg * kSeg + tid * kPerThread;          // this thread owns 16 consecutive entries
-    const float* lrow = logits + (size_t)row * V;
+    const float* lrow = logits + (size_t)job.row * V;
     const float* qptr = qrow >= 0 ? draft_probs + (size_t)qrow * V : nullptr;
+    float lv[kPerThread], qv[kPerThread];
+    if (vec && v0 + kPerThread <= V) {                     // (V % 4 == 0 and 16-byte aligned rows)
+#pragma unroll
+        for (int k4 = 0; k4 < kPerThread / 4; ++k4) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(lrow + v0 + 4 * k4);
+            lv[4 * k4] = t.x; lv[4 * k4 + 1] = t.y; lv[4 * k4 + 2] = t.z; lv[4 * k4 + 3] = t.w;
+            f32x4 q4 = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (qptr) q4 = *reinterpret_cast<const f32x4*>(qptr + v0 + 4 * k4);
+            qv[4 * k4] = q4.x; qv[4 * k4 + 1] = q4.y; qv[4 * k4 + 2] = q4.z; qv[4 * k4 + 3] = q4.w;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int v = v0 + k;
+            lv[k] = v < V ? lrow[v] : -INFINITY;
+            qv[k] = (v < V && qptr) ? qptr[v] : 0.0f;
+        }
+    }
     float rho[kPerThread];
     double mine = 0.0;
     int my_last = -1;
@@ -584,9 +787,9 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(
         const int v = v0 + k;
         rho[k] = 0.0f;
         if (v < V) {
-            const float q = qptr ? qptr[v] : (v == onehot ? 1.0f : 0.0f);
+            const float q = qptr ? qv[k] : (v == onehot ? 1.0f : 0.0f);
             float p, r;
-            residual_of(lrow[v], q, m, inv_t, z, s_tbl, p, r);
+            residual_of(lv[k], q, job.m, job.inv_t, z, rz, s_tbl, p, r);
             rho[k] = use_p ? p : r;
             if (rho[k] > 0.0f) my_last = v;
         }
@@ -616,7 +819,7 @@ __global__ __launch_bounds__(kThreads) void accept_pick_kernel(
     __syncthreads();
     if (tid == 0) {
         const int bonus = s_best != 0x7FFFFFFF ? s_best : s_last;
-        out_tokens[(size_t)i * (gamma_max + 1) + accept_len[i]] = bonus;
+        out_tokens[(size_t)i * (gamma_max + 1) + slot] = bonus;
     }
 }
 
@@ -661,21 +864,27 @@ extern "C" int spec_accept_stats(const float* logits, const int32_t* tokens, con
     carve(&w, (char*)workspace, B, M, nseg);
     const bool vec = (V % 4 == 0) && aligned(logits, 16) && (!draft_probs || aligned(draft_probs, 16));
     hipStream_t s = (hipStream_t)stream;
+    // Sampled requests: the bulk sums over all candidate rows in fp32 and an interval test, fp64 sums only on the row
+    // the bonus is drawn from (and on rows whose test the interval leaves open); or fp64 sums over every row.
+    const int filter_mode = g_accept_filter;
+    const bool filter = seeds != nullptr && filter_mode != 2;
+    const float band = !filter ? 0.0f : (filter_mode == 3 ? 0.25f : 6.103515625e-05f);   // 2^-14; 0.25 leaves most tests open
     if (blocks > 0 && !seeds) {
         // all greedy (seeds == NULL promises it) and every row's maxima are at hand: the logits are not read at all
         if (stats) hipLaunchKernelGGL(accept_reset_stats_kernel, dim3(1), dim3(64), 0, s, stats, B);
     } else {
         hipLaunchKernelGGL(accept_row_stats_kernel, dim3((nseg + kSegPerWg - 1) / kSegPerWg, M), dim3(kThreads), 0, s, logits, temperature,
-                           qo_indptr, B, V, nseg, vec, w, stats, blocks > 0);
+                           qo_indptr, B, V, nseg, vec, w, stats, blocks > 0, filter);
     }
-    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(256), 0, s, logits, tokens, draft_probs, temperature, seeds,
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, s, logits, tokens, draft_probs, temperature, seeds,
                        round, qo_indptr, accept_len, out_tokens, rollback, stats, M, V, nseg, gamma_max, w, status_flags,
-                       blk_max, blk_arg, blocks);
+                       blk_max, blk_arg, blocks, band);
     if (seeds) {   // seeds == NULL promises an all-greedy batch: nothing is ever drawn
-        hipLaunchKernelGGL(accept_residual_sums_kernel, dim3(nseg, B), dim3(kThreads), 0, s, logits, draft_probs, V,
-                           nseg, vec, w);
+        if (filter) hipLaunchKernelGGL(accept_bonus_z_kernel, dim3((nseg + kJobSegs - 1) / kJobSegs, B), dim3(kThreads), 0, s, logits, V, nseg, vec, w);
+        hipLaunchKernelGGL(accept_residual_sums_kernel, dim3((nseg + kJobSegs - 1) / kJobSegs, B), dim3(kThreads), 0, s, logits, draft_probs, V,
+                           nseg, vec, filter, w);
         hipLaunchKernelGGL(accept_pick_kernel, dim3(B), dim3(kThreads), 0, s, logits, draft_probs, accept_len,
-                           out_tokens, V, nseg, gamma_max, w);
+                           out_tokens, V, nseg, gamma_max, vec, filter, w);
     }
     return check_launch("spec_accept");
 }
@@ -763,7 +972,7 @@ extern "C" int spec_accept_tree(const float* logits, const int32_t* tokens, cons
     const bool vec = (V % 4 == 0) && aligned(logits, 16);
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(accept_row_stats_kernel, dim3((nseg + kSegPerWg - 1) / kSegPerWg, M), dim3(kThreads), 0, s, logits,
-                       (const float*)nullptr, qo_indptr, B, V, nseg, vec, w, stats, false);
+                       (const float*)nullptr, qo_indptr, B, V, nseg, vec, w, stats, false, false);
     hipLaunchKernelGGL(accept_decide_tree_kernel, dim3(B), dim3(256), 0, s, tokens, parent, qo_indptr, accept_len, out_tokens,
                        path, rollback, stats, M, V, nseg, gamma_max, w, status_flags);
     return check_launch("spec_accept_tree");

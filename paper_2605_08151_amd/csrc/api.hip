@@ -20,6 +20,7 @@ extern Tunable g_attn_plan_waves;
 extern Tunable g_attn_nr3_waves;
 extern Tunable g_attn_rows;
 extern Tunable g_attn_rows_ring;
+extern Tunable g_accept_filter;
 extern Tunable g_lm_packed_waves;
 extern Tunable g_lm_packed_wide;
 extern Tunable g_lm_packed_tile;
@@ -48,6 +49,7 @@ extern "C" int spec_set_tuning(const char* key, int value)
     if (key && std::strcmp(key, "attn_plan_waves") == 0) { specv::g_attn_plan_waves = value; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_nr3_waves") == 0) { specv::g_attn_nr3_waves = value == 4 ? 4 : 8; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_rows_ring") == 0) { specv::g_attn_rows_ring = value; return SPEC_OK; }
+    if (key && std::strcmp(key, "accept_filter") == 0) { specv::g_accept_filter = value; return SPEC_OK; }
     if (key && std::strcmp(key, "attn_rows") == 0) { specv::g_attn_rows = value; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_packed_wide") == 0) { specv::g_lm_packed_wide = value; return SPEC_OK; }
     if (key && std::strcmp(key, "lm_packed_tile") == 0) { specv::g_lm_packed_tile = value; return SPEC_OK; }

@@ -471,8 +471,19 @@ def test_greedy_ties_and_duplicates_across_segments(sv, oracle):
     assert got["accept_len"][0] == 2 and got["out_tokens"][0, 2] == 0
 
 
-@pytest.mark.parametrize("V,T,sigma", [(5, 0.8, 1.5), (1000, 0.7, 1.0), (4097, 1.0, 2.0), (32000, 0.7, 0.03), (151936, 1.0, 0.03)])
-def test_stochastic_accept_is_bit_exact(sv, oracle, V, T, sigma):
+@pytest.fixture(params=[0, 2, 3], ids=["interval_test", "fp64_sums_on_every_row", "interval_left_open"])
+def accept_filter(request, sv):
+    """How sampled requests get their normalisers: fp32 bulk sums + interval test + fp64 on the bonus row (default),
+    fp64 sums on every row, or an interval so wide that nearly every test falls through to the exact fallback.
+    The integers must be the oracle's in all three."""
+    sv.spec_set_tuning("accept_filter", request.param)
+    yield request.param
+    sv.spec_set_tuning("accept_filter", 0)
+
+
+@pytest.mark.parametrize("V,T,sigma", [(5, 0.8, 1.5), (1000, 0.7, 1.0), (4097, 1.0, 2.0), (32000, 0.7, 0.03), (151936, 1.0, 0.03),
+                                       (20000, 0.3, 6.0)])      # the last: sharp rows, exponents down to -200
+def test_stochastic_accept_is_bit_exact(sv, oracle, V, T, sigma, accept_filter):
     rng = np.random.default_rng(V + 1)
     B = 48
     gammas = rng.choice([0, 2, 4, 8], B)
@@ -489,7 +500,7 @@ def test_stochastic_accept_is_bit_exact(sv, oracle, V, T, sigma):
     assert 0 < ref["accept_len"].sum() < gammas.sum()       # both accepts and rejections occur
 
 
-def test_stochastic_one_hot_drafter_and_q_equal_p(sv, oracle):
+def test_stochastic_one_hot_drafter_and_q_equal_p(sv, oracle, accept_filter):
     rng = np.random.default_rng(5)
     V, B = 3000, 32
     gammas = np.full(B, 4)
@@ -509,7 +520,7 @@ def test_stochastic_one_hot_drafter_and_q_equal_p(sv, oracle):
 
 
 @pytest.mark.parametrize("V", [5, 10000, 151936])
-def test_sampler_without_positive_residual_draws_from_the_target(sv, oracle, V):
+def test_sampler_without_positive_residual_draws_from_the_target(sv, oracle, V, accept_filter):
     """A rejected draft whose residual max(0, p - q) is zero everywhere: (a) the draft is a masked entry (-inf logit)
     and q equals p, so 0 < 0 rejects it; (b) q = 2p, rejected whenever u >= 1/2.  The bonus then comes from p
     itself.  One and several 4096-entry segments; integers identical to the oracle's."""
@@ -543,7 +554,7 @@ def test_sampler_without_positive_residual_draws_from_the_target(sv, oracle, V):
             assert ref["out_tokens"][i, al[i]] != tokens[qo[i] + 1 + (i % 2)]
 
 
-def test_sampler_fallback_bucket_across_segments(sv, oracle):
+def test_sampler_fallback_bucket_across_segments(sv, oracle, accept_filter):
     """p = (1/2, 1/4, 1/4) on entries 10, 5000 and 9000 of a 10000-entry row (three different segments), every
     other entry masked; the draft is a masked entry and q = p: the bonus is the bucket of U(seed, round, 1, 1)."""
     V, B = 10000, 64
