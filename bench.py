@@ -57,6 +57,10 @@ def parse():
     ap.add_argument("--no-per-config", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--no-peaks", action="store_true", help="skip the linear-read and MFMA-only probes")
     ap.add_argument("--peaks", action="store_true", help="run only the two probes and print their JSON line")
+    ap.add_argument("--peaks-md", default="", metavar="PATH", help="with --peaks: also write the probes' summary (markdown) to PATH")
+    ap.add_argument("--summarize-sq", metavar="COUNTER_CSV",
+                    help="rocprofv3 --pmc counter_collection CSV of `bench.py --config NAME` with the SQ counters named in the "
+                         "summary: writes profiles/step_NAME_sq_counters.md")
     ap.add_argument("--attn-chunk", type=int, default=0, help="override keys per kv split (0 = library heuristic)")
     ap.add_argument("--fused-stats", action="store_true",
                     help="the LM head also leaves per-block maxima (spec_lm_head_stats or spec_lm_head_packed_stats) and "
@@ -130,9 +134,25 @@ def measure_peaks(torch, sv):
         torch.cuda.synchronize()
         if it >= 2:
             reads.append(src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-    del src
     out = {"hbm_linear_read_GBs": float(sorted(reads)[len(reads) // 2]), "hbm_linear_read_GBs_best": float(max(reads)),
            "hbm_probe": "spec_probe_read over 2 GiB, median of 5 launches"}
+    # the attention reads 4 KB pages (16 keys x 128 x bf16) scattered over the pool: the same 2 GiB as pages
+    n_pages = src.numel() // 4096
+    orders = {"in_order": torch.arange(n_pages, dtype=torch.int32, device="cuda"),
+              "random_order": torch.randperm(n_pages, generator=torch.Generator(device="cuda").manual_seed(1), device="cuda").to(torch.int32)}
+    for label, pages in orders.items():
+        rates = []
+        for it in range(5):
+            e0, e1 = new_event(), new_event()
+            e0.record()
+            sv.spec_probe_read_pages(src, pages, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= 2:
+                rates.append(src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        out[f"hbm_4k_pages_{label}_GBs"] = float(sorted(rates)[len(rates) // 2])
+    out["hbm_pages_probe"] = "spec_probe_read_pages over the same 2 GiB as 524288 pages of 4 KB, median of 3 launches"
+    del src, orders
     for label, const in (("random", 0), ("constant", 1)):
         rates = []
         for it in range(5):
@@ -335,6 +355,8 @@ def main():
         return summarize_counters(args)
     if args.summarize_trace:
         return summarize_trace(args)
+    if args.summarize_sq:
+        return summarize_sq(args)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives are implemented); "
               "run with --gpus 1", file=sys.stderr)
@@ -348,7 +370,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     if args.peaks:
-        print(json.dumps({"measured_peaks": measure_peaks(torch, sv), "datasheet": {"hbm_GBs": HBM_PEAK_GBS, "mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS}}))
+        rec = {"measured_peaks": measure_peaks(torch, sv), "datasheet": {"hbm_GBs": HBM_PEAK_GBS, "mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS}}
+        if args.peaks_md:
+            write_peaks_md(args.peaks_md, rec)
+        print(json.dumps(rec))
         return
     if args.attn_chunk:
         sv.spec_set_tuning("attn_chunk", args.attn_chunk)
@@ -552,6 +577,68 @@ def summarize_counters(args):
                     "key = workload:kernel; written by `bench.py --summarize-counters`; tables in step_<workload>_hbm_traffic.md")
     json.dump(dict(sorted(old.items())), open(TRAFFIC_JSON, "w"), indent=1)
     print(open(md).read())
+
+
+SQ_COUNTERS = ("SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_WAIT_INST_ANY "
+               "SQ_ACTIVE_INST_VALU SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE GRBM_GUI_ACTIVE")
+
+
+def summarize_sq(args):
+    name = args.config
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in csv.DictReader(open(args.summarize_sq)):
+        if "specv::" in r["Kernel_Name"]:
+            k = r["Kernel_Name"].split("(")[0].replace("void ", "")
+            agg[k][r["Counter_Name"]].append(float(r["Counter_Value"]))
+            if r["Counter_Name"] == "GRBM_GUI_ACTIVE":
+                agg[k]["_us"].append((float(r["End_Timestamp"]) - float(r["Start_Timestamp"])) / 1e3)
+    cmd = args.profile_cmd or f"python3 bench.py --config {name} --steps 5 --warmup 2 --no-cpu-baseline --no-per-config --no-peaks"
+    md = os.path.join(ROOT, "profiles", f"step_{name}_sq_counters.md")
+    rows = []
+    for k, v in agg.items():
+        a = {c: sum(x) / len(x) for c, x in v.items()}
+        if a.get("_us", 0.0) < 4.0 or "probe" in k or "pack_kernel" in k:
+            continue
+        cyc, wc = a["GRBM_GUI_ACTIVE"] / 8, max(a["SQ_WAVE_CYCLES"], 1.0)
+        rows.append((a["_us"], f"| {k} | {len(v['_us'])} | {a['_us']:.1f} | {cyc / a['_us'] / 1e3:.2f} | "
+                     f"{a['SQ_VALU_MFMA_BUSY_CYCLES'] / (cyc * 1024) * 100:.1f} % | {a['SQ_INSTS_VALU_MFMA_MOPS_BF16'] * 512:.3e} | "
+                     f"{a['SQ_ACTIVE_INST_VALU'] / wc:.2f} | {a['SQ_WAIT_INST_ANY'] / wc:.2f} | {a['SQ_WAIT_ANY'] / wc:.2f} | "
+                     f"{a['SQ_LDS_IDX_ACTIVE']:.3e} | {a['SQ_LDS_BANK_CONFLICT'] / max(a['SQ_LDS_IDX_ACTIVE'], 1) * 100:.1f} % |\n"))
+    with open(md, "w") as o:
+        o.write(f"# Verification step, workload '{name}': wave, MFMA and LDS counters (rocprofv3 --pmc)\n\n")
+        o.write("Commands (on the MI355X box, from the repository root):\n\n")
+        o.write("    cd /tmp && export TMPDIR=/tmp && cd $GRAFT_REPO_ROOT\n")
+        o.write(f"    rocprofv3 --pmc {SQ_COUNTERS} --output-format csv -d gpurun_out/pmc_sq -o {name} -- {cmd}\n")
+        o.write(f"    python3 bench.py --config {name} --summarize-sq gpurun_out/pmc_sq/{name}_counter_collection.csv\n\n")
+        o.write("Reading: launches of 4 us or more, averages per launch.  GRBM_GUI_ACTIVE is summed over the 8 XCDs (/8 = cycles of the "
+                "launch, 'clock' = cycles / us; it also counts the few microseconds around a dispatch, so the clock of a short kernel reads "
+                "high).  SQ_VALU_MFMA_BUSY_CYCLES is summed over the 1024 SIMDs; one MFMA MOP is 512 flop.  VALU / wait columns are "
+                "fractions of SQ_WAVE_CYCLES (cycles summed over resident waves): 'wait inst' = stalled at a wait-count instruction, "
+                "'wait any' = waiting for anything (barriers included).\n\n")
+        o.write("| kernel | launches | us | clock GHz | MFMA busy (of 1024 SIMDs) | MFMA flop | VALU active | wait inst | wait any | "
+                "LDS active cycles (sum) | of which bank conflicts |\n|---|---|---|---|---|---|---|---|---|---|---|\n")
+        for _, line in sorted(rows, reverse=True):
+            o.write(line)
+    print(open(md).read())
+
+
+def write_peaks_md(path, rec):
+    p = rec["measured_peaks"]
+    with open(path, "w") as o:
+        o.write("# Measured ceilings of the MI355X box (probes of the library, HIP events on the launch stream)\n\n")
+        o.write("Command (on the MI355X box, from the repository root):\n\n    python3 bench.py --peaks --peaks-md gpurun_out/peaks.md\n\n")
+        o.write("| probe | measured | datasheet | ratio |\n|---|---|---|---|\n")
+        hb, mf = rec["datasheet"]["hbm_GBs"], rec["datasheet"]["mfma_bf16_TFLOPs"]
+        o.write(f"| linear read of 2 GiB (`spec_probe_read`, 16-byte loads, 4 KB per workgroup step), median | {p['hbm_linear_read_GBs']:.0f} GB/s | {hb:.0f} GB/s | {p['hbm_linear_read_GBs'] / hb:.3f} |\n")
+        o.write(f"| the same, best launch | {p['hbm_linear_read_GBs_best']:.0f} GB/s | {hb:.0f} GB/s | {p['hbm_linear_read_GBs_best'] / hb:.3f} |\n")
+        o.write(f"| the same 2 GiB as 4 KB pages through an index list, in order (`spec_probe_read_pages`) | {p['hbm_4k_pages_in_order_GBs']:.0f} GB/s | {hb:.0f} GB/s | {p['hbm_4k_pages_in_order_GBs'] / hb:.3f} |\n")
+        o.write(f"| 4 KB pages in a random permutation (what a paged K/V pool looks like) | {p['hbm_4k_pages_random_order_GBs']:.0f} GB/s | {hb:.0f} GB/s | {p['hbm_4k_pages_random_order_GBs'] / hb:.3f} |\n")
+        o.write(f"| MFMA only, v_mfma_f32_16x16x32_bf16, random bf16 operands (`spec_probe_mfma`) | {p['mfma_bf16_TFLOPs_random_operands']:.0f} TFLOP/s | {mf:.0f} TFLOP/s | {p['mfma_bf16_TFLOPs_random_operands'] / mf:.3f} |\n")
+        o.write(f"| MFMA only, constant operands | {p['mfma_bf16_TFLOPs_constant_operands']:.0f} TFLOP/s | {mf:.0f} TFLOP/s | {p['mfma_bf16_TFLOPs_constant_operands'] / mf:.3f} |\n")
+        o.write(f"\n{p['hbm_probe']}; {p['hbm_pages_probe']}; {p['mfma_probe']}.\n")
+        o.write("\nThe MFMA rate depends on the operand data (toggling costs power, and the clock follows): the random-operand figure "
+                "is the ceiling a GEMM on real data can be held against.  `bench.py` prints `frac_of_measured_peak` beside every "
+                "datasheet `frac`: HBM-bound calls against the linear read, the LM head against the random-operand MFMA rate.\n")
 
 
 def summarize_trace(args):
