@@ -1302,10 +1302,21 @@ def _sampled_logits_check(oracle, b, gl, n_cols=192, seed=0):
     _close(gl[:, cols], ref, "sampled logits")
 
 
+def _all_logits_check(oracle, b, gl, what):
+    """Every logit against the oracle, 256 rows at a time: the contract's bound, the scaled bound, and the bound that
+    fp32 accumulation over H products allows (1e-5 sqrt(H) max|ref|)."""
+    H = b["hidden"].shape[1]
+    Wb = wl.bf16_bits(b["W"])
+    for lo in range(0, gl.shape[0], 256):
+        ref = oracle.lm_head(wl.bf16_bits(b["hidden"][lo:lo + 256]), Wb)
+        _close(gl[lo:lo + 256], ref, f"{what}, rows {lo}..")
+        assert np.abs(gl[lo:lo + 256] - ref).max() <= 1e-5 * np.sqrt(H) * np.abs(ref).max(), what
+
+
 @pytest.mark.parametrize("name", ["mid", "stochastic", "long"])
 def test_full_size_configuration(sv, oracle, name):
     """The mid, stochastic and long workloads at full size, in the launch configuration bench.py times:
-    attention against the oracle on every row, logits on sampled vocabulary entries, acceptance and
+    attention against the oracle on every row, every logit against the oracle, acceptance and
     commit bit-exact on the GPU's own logits."""
     cfg = wl.CONFIGS[name]
     stochastic = cfg.temperature != ("const", 0.0)
@@ -1315,15 +1326,14 @@ def test_full_size_configuration(sv, oracle, name):
     # every logit, against the independent row-major kernels: both add a row's products in the same order
     packed_logits = step.logits.clone()
     assert torch.equal(step.lm_head(b["hidden"], b["W"]), packed_logits)
-    if name == "mid":
-        # the benchmark's own workload: every one of the 160 x 151936 logits against the oracle (a few seconds of host time)
-        _close(gl, oracle.lm_head(wl.bf16_bits(b["hidden"]), wl.bf16_bits(b["W"])), "mid logits, all of them")
+    # and every one of the M x 151936 logits against the oracle (mid, long: a few seconds of host time; stochastic: ~15 s)
+    _all_logits_check(oracle, b, gl, f"{name} logits, all of them")
 
 
 def test_full_size_hybrid_mix_properties(sv, oracle):
     """The hybrid workload (B=256, gamma in {0,2,4,8}, lognormal contexts up to 32k, half sampled):
-    attention of the whole batch against the oracle (the device-built work list at full size), logits on
-    sampled vocabulary entries, acceptance and commit bit-exact on the whole batch."""
+    attention of the whole batch against the oracle (the device-built work list at full size), every logit
+    against the oracle, acceptance and commit bit-exact on the whole batch."""
     cfg = wl.CONFIGS["hybrid"]
     b = wl.make_batch(cfg, device="cuda")
     step = _step(b, cfg)
@@ -1339,6 +1349,8 @@ def test_full_size_hybrid_mix_properties(sv, oracle):
     torch.cuda.synchronize()
     gl = logits.cpu().numpy()
     _sampled_logits_check(oracle, b, gl, n_cols=64)
+    # all 1206 x 151936 logits of the large-tile kernel against the oracle (~30 s of host time on 16 cores)
+    _all_logits_check(oracle, b, gl, "hybrid logits, all of them")
     temp = b["temperature"].cpu().numpy()
     tokens_g, _ = wl.draft_tokens_greedy(cfg, b["qo_indptr"], torch.from_numpy(gl.argmax(1)))
     dp, tokens_s = wl.draft_probs_noisy(cfg, b["qo_indptr"], logits)
