@@ -88,6 +88,32 @@ def test_attention_is_split_invariant(sv, oracle, chunk):
     _close(out.float().cpu().numpy(), _oracle_attn(oracle, b), f"chunk {chunk}", sharp=True)
 
 
+@pytest.mark.parametrize("tuning", [{"attn_rows": 1}, {"attn_rows": 2}, {"attn_rows_ring": 4}, {"attn_rows": 2, "attn_rows_ring": 4}],
+                         ids=["wave_per_key_block", "row_split_from_2_tiles", "ring_of_4", "both"])
+@pytest.mark.parametrize("case", [c for c in ATTN_CASES if c[0] in ("sharp_g8", "sharp_g4", "max_rows", "g16", "short_ctx")],
+                         ids=lambda c: c[0])
+def test_attention_kernel_variants_match_oracle(sv, oracle, case, tuning):
+    """The two decompositions of the attention kernel (one wave per key block and all rows; one wave per row tile and shared
+    K/V stages) and the ring depths of the latter, each forced where it is not the default, split into several chunks."""
+    name, B, gammas, ctx, Hq, Hkv, sq = case
+    cfg = wl.VerifyConfig(name, 21, B, gammas, ctx, Hq, Hkv, 64, 64, sigma_qkv=sq)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    keys = dict(tuning, attn_chunk=256)
+    for k, v in keys.items():
+        sv.spec_set_tuning(k, v)
+    try:
+        step = _step(b, cfg)
+        out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
+        torch.cuda.synchronize()
+    finally:
+        for k in keys:
+            sv.spec_set_tuning(k, 0)
+    ref, ref_lse = _oracle_attn(oracle, b, want_lse=True)
+    _close(out.float().cpu().numpy(), ref, f"{name} {tuning}", sharp=True)
+    np.testing.assert_allclose(step.lse.cpu().numpy(), ref_lse, rtol=2e-3, atol=2e-3)
+    assert int(step.status.cpu()) == 0
+
+
 PLAN_CASES = ATTN_CASES + [
     ("plan_split", 4, (0, 4, 8), ("uniform", 900, 2500), 8, 1, 1.0),
     ("plan_long_few", 2, (4,), ("uniform", 5000, 9000), 8, 1, 1.0),
