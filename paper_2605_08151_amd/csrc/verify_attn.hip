@@ -558,6 +558,13 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
         sAnc[r] = m;
     }
     __syncthreads();                                      // page ids and masks visible
+    // The Q fragments came by ordinary loads.  The compiler cannot see the direct loads below (inline assembly), and with
+    // some of them always in flight (rings deeper than two) it would make the loop wait for "all loads" at the first use
+    // of a fragment in every stage, which serialises the ring (measured 230 against 187 us).  Waiting once here and handing
+    // the registers through an empty statement tells it that nothing is pending on them.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) asm volatile("" : "+v"(qf[s]));
 
     // ---- stage st of the chunk (keys kbeg + 32 st ..): its 16 direct loads are dealt to the waves, kIssue each; slots past the
     // range read page 0 (never used), so that the wait counts are constants ----
@@ -567,6 +574,9 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
         const int t0s = kbeg + st * 32;
 #pragma unroll
         for (int k = 0; k < kIssue; ++k) {
+            // with a ring of two the wait in front of a stage is "all of this wave's loads", so a surplus slot may
+            // simply stay empty; deeper rings count loads per stage, there the surplus slots repeat the last load
+            if (kRowsStages == 2 && wave * kIssue + k > 15) break;
             const int q = min(wave * kIssue + k, 15);     // load q of the stage: which of K/V, which page, which 4 rows
             const int isv = q >> 3, pg = (q >> 2) & 1, q4 = q & 3;
             const int t0 = t0s + pg * kP;
