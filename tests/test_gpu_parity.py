@@ -526,6 +526,29 @@ def test_stochastic_accept_is_bit_exact(sv, oracle, V, T, sigma, accept_filter):
     assert 0 < ref["accept_len"].sum() < gammas.sum()       # both accepts and rejections occur
 
 
+@pytest.mark.parametrize("V,B,gamma", [(270000, 6, 3), (2200000, 3, 2), (1000, 5, 63), (4100, 4, 40)],
+                         ids=["66_segments", "538_segments_unstaged", "64_rows", "41_rows_2_segments"])
+def test_stochastic_accept_wide_vocabularies_and_deep_drafts(sv, oracle, V, B, gamma, accept_filter):
+    """More than 64 segments per row (the segment walks go round their 64-lane loops more than once), more than 512 (the
+    draw reads the segment sums in place), and up to 64 candidate rows per request (every lane of the decision wave holds
+    a draft; rows beyond the sixteenth are merged in a second turn of the waves)."""
+    rng = np.random.default_rng(V + gamma)
+    gammas = np.full(B, gamma)
+    gammas[0] = max(1, gamma // 2)
+    qo = _qo(gammas)
+    logits = rng.normal(0, 1.0, (qo[-1], V)).astype(np.float32)
+    cfg = wl.VerifyConfig("w", V % 1000, B, (gamma,), ("const", 1), 8, 1, 64, V)
+    dp, tokens = wl.draft_probs_noisy(cfg, torch.from_numpy(qo), torch.from_numpy(logits), noise_std=0.3)
+    seeds = rng.integers(0, 2 ** 63, B, dtype=np.uint64)
+    temp = np.full(B, 0.8, np.float32)
+    if B > 3:
+        temp[1] = 0.0
+    got, ref = _accept_both(sv, oracle, logits, tokens.numpy(), dp.numpy(), temp, seeds, 5, qo, gamma)
+    _assert_same(got, ref, gammas)
+    assert got["status"] == 0
+    assert ref["accept_len"].sum() > 0
+
+
 def test_stochastic_one_hot_drafter_and_q_equal_p(sv, oracle, accept_filter):
     rng = np.random.default_rng(5)
     V, B = 3000, 32
