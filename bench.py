@@ -65,6 +65,9 @@ def parse():
     ap.add_argument("--fused-stats", action="store_true",
                     help="the LM head also leaves per-block maxima (spec_lm_head_stats or spec_lm_head_packed_stats) and "
                          "greedy acceptance reads those instead of the logits (spec_accept_stats); same outputs")
+    ap.add_argument("--summaries", choices=("auto", "on", "off"), default="auto",
+                    help="block summaries from the large-tile LM head (spec_lm_head_packed_summary + spec_accept_summary) when the "
+                         "batch has more than 160 rows: on, off, or auto = with --fused-stats")
     ap.add_argument("--lm-weights", choices=("auto", "packed", "rowmajor"), default="auto",
                     help="layout of the vocabulary matrix: packed (spec_lm_head_packed; re-laid once before the timed "
                          "region, as at model load) or rowmajor (spec_lm_head); auto = packed whenever the kernel takes "
@@ -214,6 +217,9 @@ def measure(args, cfg_name, steps, warmup, extras):
     states = [(b["page_table"].clone(), b["seq_lens"].clone(), b["free_list"].clone(), b["free_count"].clone())
               for _ in range(total)]
     fused = args.fused_stats            # same outputs; greedy acceptance reads the LM head's block maxima instead of the logits
+    # more than 160 rows on packed weights: the large-tile LM head can leave block summaries (maxima and exponential sums)
+    # from which acceptance works without scanning the logits again; same outputs
+    summaries = packed and args.summaries != "off" and step.sblocks > 0 and (args.summaries == "on" or fused)
 
     def run(k, events=None):
         """One step.  `events`: None, or five events recorded around the four calls (None entries are skipped)."""
@@ -223,7 +229,9 @@ def measure(args, cfg_name, steps, warmup, extras):
         if events[0]: events[0].record()
         step.attn(b["q"], kc, vc, pt, sl, qo, b["scale"], want_lse=False)
         if events[1]: events[1].record()
-        if fused and packed:
+        if summaries:
+            step.lm_head_packed_summary(b["hidden"], Wp, b["temperature"], qo)
+        elif fused and packed:
             step.lm_head_packed_stats(b["hidden"], Wp)
         elif fused:
             step.lm_head_stats(b["hidden"], b["W"])
@@ -232,7 +240,9 @@ def measure(args, cfg_name, steps, warmup, extras):
         else:
             step.lm_head(b["hidden"], b["W"])
         if events[2]: events[2].record()
-        if fused and packed:
+        if summaries:
+            step.accept_summary(tokens, draft_probs, b["temperature"], seeds, 0, qo)
+        elif fused and packed:
             step.accept_packed_stats(tokens, draft_probs, b["temperature"], seeds, 0, qo)
         elif fused:
             step.accept_stats(tokens, draft_probs, b["temperature"], seeds, 0, qo)

@@ -213,6 +213,26 @@ int spec_lm_head_packed_stats_blocks(int M, int H, int V);
 int spec_lm_head_packed_stats(const void* hidden, const void* Wp, float* logits, int M, int H, int V,
                               float* blk_max, int32_t* blk_arg, void* stream);
 
+/* spec_lm_head_packed_summary — spec_lm_head_packed for more than 160 rows that also leaves what acceptance needs
+ * from each row of logits, so that no row has to be read again (same operation and passage as spec_lm_head; the
+ * consumer is spec_accept_summary).  A block is a run of at most 64 consecutive vocabulary entries; blocks cover
+ * increasing ranges.
+ *   blocks = spec_lm_head_packed_summary_blocks(M, H, V) (host): blocks per row; 0 when this call does not take the
+ *     shape (M <= 160, H not a multiple of 256, or V not a multiple of 4) - use spec_lm_head_packed then.
+ *   temperature [B] fp32, qo_indptr [B + 1] int32 (device): as for spec_accept; they say which rows are sampled.
+ *   blk_max  [M, blocks] fp32: the block's maximum; NaN if the block holds a NaN.
+ *   blk_sum  [M, blocks] fp32: for the rows of requests with temperature T > 0 the sum over the block of
+ *     2^((l - blk_max) * log2(e) / T) (fp32 arithmetic, relative error < 2^-16), else 0.
+ *   blk_span [blocks, 2] int32: first entry and number of entries of every block (0 entries: the slot is unused and
+ *     its blk_max / blk_sum are not written).
+ *   All four are device memory owned by the caller.  Logits as spec_lm_head_packed, bit for bit.  Errors as there;
+ *   SPEC_ESHAPE for a shape with blocks == 0. */
+int spec_lm_head_packed_summary_blocks(int M, int H, int V);
+
+int spec_lm_head_packed_summary(const void* hidden, const void* Wp, float* logits, int M, int H, int V,
+                                const float* temperature, const int32_t* qo_indptr, int B,
+                                float* blk_max, float* blk_sum, int32_t* blk_span, void* stream);
+
 /* ---------------------------------------------------------------------------
  * spec_accept — accepted length and bonus token per request (Method,
  * "Rollback-Based Mode Selection": after the verification pass the target
@@ -272,6 +292,20 @@ int spec_accept_static(const float* logits, const int32_t* tokens, const float* 
                        int32_t* accept_len, int32_t* out_tokens, uint8_t* rollback, int32_t* stats,
                        int B, int M, int V, int gamma_max,
                        int32_t* status_flags, void* stream);
+
+/* spec_accept with the block summaries of spec_lm_head_packed_summary (blocks == 0: identical to spec_accept).  No
+ * row of logits is scanned: a greedy row finds its argmax inside the one block that holds the row maximum (64 logits
+ * are read), a sampled row takes the estimate of its normaliser from the block sums, which the interval test of
+ * spec_accept then uses (the "accept_filter" key cannot turn that off here); the one row per sampled request that
+ * the bonus is drawn from is still summed in fp64 from the logits.  Same outputs, flags and errors as spec_accept. */
+int spec_accept_summary(const float* logits, const int32_t* tokens, const float* draft_probs,
+                        const float* temperature, const uint64_t* seeds, uint32_t round,
+                        const int32_t* qo_indptr,
+                        int32_t* accept_len, int32_t* out_tokens, uint8_t* rollback, int32_t* stats,
+                        int B, int M, int V, int gamma_max,
+                        const float* blk_max, const float* blk_sum, const int32_t* blk_span, int blocks,
+                        int32_t* status_flags,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* spec_accept with the block statistics of spec_lm_head_stats (blk_max, blk_arg, blocks as described there;
  * blocks == 0: identical to spec_accept).  Requests with temperature 0 take their row maxima from the

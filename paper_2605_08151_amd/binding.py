@@ -24,6 +24,7 @@ EXPORTS = (
     "spec_lm_head_packed_bytes", "spec_lm_head_pack", "spec_lm_head_packed",
     "spec_lm_head_packed_stats_blocks", "spec_lm_head_packed_stats",
     "spec_probe_read", "spec_probe_read_pages", "spec_probe_mfma", "spec_accept_static",
+    "spec_lm_head_packed_summary_blocks", "spec_lm_head_packed_summary", "spec_accept_summary",
 )
 
 FLAG_BAD_PAGE, FLAG_BAD_LENGTH, FLAG_BAD_LOGITS, FLAG_BAD_TOKEN, FLAG_FREE_OVERFLOW, FLAG_NO_SEED = 1, 2, 4, 8, 16, 32
@@ -75,6 +76,12 @@ def _load():
     lib.spec_lm_head_packed_stats_blocks.argtypes = [i32] * 3
     lib.spec_lm_head_packed_stats.restype = i32
     lib.spec_lm_head_packed_stats.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.spec_lm_head_packed_summary_blocks.restype = i32
+    lib.spec_lm_head_packed_summary_blocks.argtypes = [i32] * 3
+    lib.spec_lm_head_packed_summary.restype = i32
+    lib.spec_lm_head_packed_summary.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, vp, vp]
+    lib.spec_accept_summary.restype = i32
+    lib.spec_accept_summary.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.spec_accept_stats.restype = i32
     lib.spec_accept_stats.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, vp, vp, sz, vp]
     lib.spec_verify_attn_tree.restype = i32
@@ -228,6 +235,25 @@ def spec_lm_head_packed_stats(hidden, Wp, logits, blk_max, blk_arg):
                                           M, H, V, _ptr(blk_max, torch.float32), _ptr(blk_arg, torch.int32), _stream()))
 
 
+def spec_lm_head_packed_summary_blocks(M, H, V):
+    return int(_lib.spec_lm_head_packed_summary_blocks(int(M), int(H), int(V)))
+
+
+def spec_lm_head_packed_summary(hidden, Wp, logits, temperature, qo_indptr, blk_max, blk_sum, blk_span):
+    M, H = hidden.shape
+    V = logits.shape[1]
+    B = qo_indptr.shape[0] - 1
+    assert logits.shape[0] == M and Wp.numel() * Wp.element_size() == spec_lm_head_packed_bytes(V, H)
+    blocks = spec_lm_head_packed_summary_blocks(M, H, V)
+    assert blocks > 0, "spec_lm_head_packed_summary does not take this shape"
+    assert temperature.numel() == B and tuple(blk_max.shape) == (M, blocks) and tuple(blk_sum.shape) == (M, blocks)
+    assert tuple(blk_span.shape) == (blocks, 2)
+    _check(_lib.spec_lm_head_packed_summary(_ptr(hidden, torch.bfloat16), _ptr(Wp, torch.bfloat16), _ptr(logits, torch.float32),
+                                            M, H, V, _ptr(temperature, torch.float32), _ptr(qo_indptr, torch.int32), B,
+                                            _ptr(blk_max, torch.float32), _ptr(blk_sum, torch.float32),
+                                            _ptr(blk_span, torch.int32), _stream()))
+
+
 def spec_accept_workspace_bytes(B, M, V, gamma_max):
     return int(_lib.spec_accept_workspace_bytes(B, M, V, gamma_max))
 
@@ -269,6 +295,24 @@ def spec_accept_stats(logits, tokens, draft_probs, temperature, seeds, round_, q
         _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), _ptr(rollback, torch.uint8),
         _ptr(stats, torch.int32), B, M, V, int(gamma_max),
         _ptr(blk_max, torch.float32) if blocks else None, _ptr(blk_arg, torch.int32) if blocks else None, int(blocks),
+        _ptr(status_flags, torch.int32),
+        _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
+
+
+def spec_accept_summary(logits, tokens, draft_probs, temperature, seeds, round_, qo_indptr, accept_len, out_tokens, rollback,
+                        stats, gamma_max, blk_max, blk_sum, blk_span, blocks, status_flags, workspace):
+    M, V = logits.shape
+    B = qo_indptr.shape[0] - 1
+    assert tuple(out_tokens.shape) == (B, gamma_max + 1)
+    assert blocks == 0 or (tuple(blk_max.shape) == (M, blocks) and tuple(blk_sum.shape) == (M, blocks)
+                           and tuple(blk_span.shape) == (blocks, 2))
+    _check(_lib.spec_accept_summary(
+        _ptr(logits, torch.float32), _ptr(tokens, torch.int32), _ptr(draft_probs, torch.float32),
+        _ptr(temperature, torch.float32), _ptr(seeds, torch.int64), int(round_), _ptr(qo_indptr, torch.int32),
+        _ptr(accept_len, torch.int32), _ptr(out_tokens, torch.int32), _ptr(rollback, torch.uint8),
+        _ptr(stats, torch.int32), B, M, V, int(gamma_max),
+        _ptr(blk_max, torch.float32) if blocks else None, _ptr(blk_sum, torch.float32) if blocks else None,
+        _ptr(blk_span, torch.int32) if blocks else None, int(blocks),
         _ptr(status_flags, torch.int32),
         _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream()))
 

@@ -288,6 +288,17 @@ __global__ void accept_reset_stats_kernel(int32_t* __restrict__ stats, int B)
 }
 
 // ---- 2. per-request decision -----------------------------------------------------------------
+// Block summaries of the large-tile LM head (LmSummary in common.h), when the caller has them: per row and block of
+// at most 64 entries the maximum and, for sampled rows, the fp32 sum of 2^((l - max) log2(e)/T); blk_span = {first entry,
+// entries} per block.  With them no row of logits is scanned: a greedy row looks its argmax up inside the one block that
+// holds the row maximum, a sampled row gets its estimated normaliser from the block sums.
+struct AcceptSummary {
+    const float* blk_max;
+    const float* blk_sum;
+    const int32_t* blk_span;
+    int blocks;
+};
+
 constexpr int kDecideThreads = 1024;   // 16 waves: the rows of a request (gamma + 1 <= 16 in practice) are merged side by side
 
 __global__ __launch_bounds__(kDecideThreads) void accept_decide_kernel(
@@ -296,7 +307,7 @@ __global__ __launch_bounds__(kDecideThreads) void accept_decide_kernel(
     const int32_t* __restrict__ qo_indptr, int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens,
     uint8_t* __restrict__ rollback, int32_t* __restrict__ stats, int M, int V, int nseg, int gamma_max,
     AcceptWorkspace w, int32_t* __restrict__ status_flags,
-    const float* __restrict__ blk_max, const int32_t* __restrict__ blk_arg, int nblk, float band)
+    const float* __restrict__ blk_max, const int32_t* __restrict__ blk_arg, int nblk, float band, AcceptSummary sum)
 {
     __shared__ double s_m[kMaxRows], s_z[kMaxRows];
     __shared__ int s_arg[kMaxRows], s_bad[kMaxRows];
@@ -316,6 +327,56 @@ __global__ __launch_bounds__(kDecideThreads) void accept_decide_kernel(
         const size_t base = (size_t)(r0 + j) * nseg;
         float m = -INFINITY;
         int arg = 0x7FFFFFFF, bad = 0;
+        if (sum.blocks > 0) {
+            const size_t bb = (size_t)(r0 + j) * sum.blocks;
+            int mb = 0x7FFFFFFF;                          // lowest block that holds the row maximum
+            for (int s0 = lane; s0 < sum.blocks; s0 += 64 * 8) {
+                float sm[8];
+                int cnt[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int s = s0 + 64 * u;
+                    cnt[u] = s < sum.blocks ? sum.blk_span[2 * s + 1] : 0;
+                    sm[u] = s < sum.blocks ? sum.blk_max[bb + s] : -INFINITY;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (cnt[u] <= 0) continue;            // a slot without entries: its records were never written
+                    bad |= (sm[u] != sm[u]);
+                    if (sm[u] > m) { m = sm[u]; mb = s0 + 64 * u; }     // (ascending s: ties keep the lower block)
+                }
+            }
+            wave_max_arg(m, mb);
+            bad = __any(bad) || !(m > -INFINITY && m < INFINITY);
+            double z = 0.0;
+            if (!bad && T == 0.0f) {
+                const int first = sum.blk_span[2 * mb], count = sum.blk_span[2 * mb + 1];
+                const float x = lane < count ? logits[(size_t)(r0 + j) * V + first + lane] : -INFINITY;
+                const unsigned long long hit = __ballot(x == m);
+                arg = first + (hit ? __ffsll((long long)hit) - 1 : 0);
+            } else if (!bad) {
+                // the block sums are fp32 estimates: rescaling them with the hardware exponential (another ~1e-5 at
+                // most for exponents down to -64, nothing below) keeps the total inside the band of the interval test
+                const float c = (float)(1.4426950408889634 / Td);
+                for (int s0 = lane; s0 < sum.blocks; s0 += 64 * 8) {
+                    float sm[8], sz[8];
+                    int cnt[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int s = s0 + 64 * u;
+                        cnt[u] = s < sum.blocks ? sum.blk_span[2 * s + 1] : 0;
+                        sm[u] = s < sum.blocks ? sum.blk_max[bb + s] : -INFINITY;
+                        sz[u] = s < sum.blocks ? sum.blk_sum[bb + s] : 0.0f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (cnt[u] > 0 && sm[u] > -INFINITY) z += (double)(sz[u] * __builtin_amdgcn_exp2f((sm[u] - m) * c));
+                }
+                z = wave_sum(z);
+            }
+            if (lane == 0) { s_m[j] = (double)m; s_z[j] = z; s_arg[j] = arg; s_bad[j] = bad; }
+            continue;
+        }
         if (from_blocks) {
             // ~V/128 blocks per row: eight loads in flight per lane, or the walk is one memory latency per 64 blocks
             const size_t bb = (size_t)(r0 + j) * nblk;
@@ -835,12 +896,12 @@ extern "C" size_t spec_accept_workspace_bytes(int B, int M, int V, int gamma_max
     return specv::carve(&w, nullptr, B, M, accept_nseg(V));
 }
 
-extern "C" int spec_accept_stats(const float* logits, const int32_t* tokens, const float* draft_probs,
-                                 const float* temperature, const uint64_t* seeds, uint32_t round,
-                                 const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
-                                 uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
-                                 const float* blk_max, const int32_t* blk_arg, int blocks,
-                                 int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
+static int accept_impl(const float* logits, const int32_t* tokens, const float* draft_probs,
+                       const float* temperature, const uint64_t* seeds, uint32_t round,
+                       const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
+                       uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                       const float* blk_max, const int32_t* blk_arg, int blocks, specv::AcceptSummary sum,
+                       int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
 {
     using namespace specv;
     if (B < 0 || M < 0 || V <= 0 || gamma_max < 0 || blocks < 0)
@@ -867,10 +928,11 @@ extern "C" int spec_accept_stats(const float* logits, const int32_t* tokens, con
     // Sampled requests: the bulk sums over all candidate rows in fp32 and an interval test, fp64 sums only on the row
     // the bonus is drawn from (and on rows whose test the interval leaves open); or fp64 sums over every row.
     const int filter_mode = g_accept_filter;
-    const bool filter = seeds != nullptr && filter_mode != 2;
+    const bool filter = seeds != nullptr && (filter_mode != 2 || sum.blocks > 0);   // block sums are estimates: the interval test is needed
     const float band = !filter ? 0.0f : (filter_mode == 3 ? 0.25f : 6.103515625e-05f);   // 2^-14; 0.25 leaves most tests open
-    if (blocks > 0 && !seeds) {
-        // all greedy (seeds == NULL promises it) and every row's maxima are at hand: the logits are not read at all
+    if (sum.blocks > 0 || (blocks > 0 && !seeds)) {
+        // every row's summary is at hand (or: all greedy, seeds == NULL promises it, and every row's maxima are):
+        // no row of logits is scanned
         if (stats) hipLaunchKernelGGL(accept_reset_stats_kernel, dim3(1), dim3(64), 0, s, stats, B);
     } else {
         hipLaunchKernelGGL(accept_row_stats_kernel, dim3((nseg + kSegPerWg - 1) / kSegPerWg, M), dim3(kThreads), 0, s, logits, temperature,
@@ -878,7 +940,7 @@ extern "C" int spec_accept_stats(const float* logits, const int32_t* tokens, con
     }
     hipLaunchKernelGGL(accept_decide_kernel, dim3(B), dim3(kDecideThreads), 0, s, logits, tokens, draft_probs, temperature, seeds,
                        round, qo_indptr, accept_len, out_tokens, rollback, stats, M, V, nseg, gamma_max, w, status_flags,
-                       blk_max, blk_arg, blocks, band);
+                       blk_max, blk_arg, blocks, band, sum);
     if (seeds) {   // seeds == NULL promises an all-greedy batch: nothing is ever drawn
         if (filter) hipLaunchKernelGGL(accept_bonus_z_kernel, dim3((nseg + kJobSegs - 1) / kJobSegs, B), dim3(kThreads), 0, s, logits, V, nseg, vec, w);
         hipLaunchKernelGGL(accept_residual_sums_kernel, dim3((nseg + kJobSegs - 1) / kJobSegs, B), dim3(kThreads), 0, s, logits, draft_probs, V,
@@ -887,6 +949,32 @@ extern "C" int spec_accept_stats(const float* logits, const int32_t* tokens, con
                            out_tokens, V, nseg, gamma_max, vec, filter, w);
     }
     return check_launch("spec_accept");
+}
+
+extern "C" int spec_accept_stats(const float* logits, const int32_t* tokens, const float* draft_probs,
+                                 const float* temperature, const uint64_t* seeds, uint32_t round,
+                                 const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
+                                 uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                                 const float* blk_max, const int32_t* blk_arg, int blocks,
+                                 int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return accept_impl(logits, tokens, draft_probs, temperature, seeds, round, qo_indptr, accept_len, out_tokens, rollback, stats,
+                       B, M, V, gamma_max, blk_max, blk_arg, blocks, specv::AcceptSummary{}, status_flags, workspace,
+                       workspace_bytes, stream);
+}
+
+extern "C" int spec_accept_summary(const float* logits, const int32_t* tokens, const float* draft_probs,
+                                   const float* temperature, const uint64_t* seeds, uint32_t round,
+                                   const int32_t* qo_indptr, int32_t* accept_len, int32_t* out_tokens,
+                                   uint8_t* rollback, int32_t* stats, int B, int M, int V, int gamma_max,
+                                   const float* blk_max, const float* blk_sum, const int32_t* blk_span, int blocks,
+                                   int32_t* status_flags, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (blocks < 0 || (blocks > 0 && (!blk_max || !blk_sum || !blk_span)))
+        return specv::fail(SPEC_EINVAL, "spec_accept_summary: blocks=%d without block summaries", blocks);
+    specv::AcceptSummary sum{blk_max, blk_sum, blk_span, blocks};
+    return accept_impl(logits, tokens, draft_probs, temperature, seeds, round, qo_indptr, accept_len, out_tokens, rollback, stats,
+                       B, M, V, gamma_max, nullptr, nullptr, 0, sum, status_flags, workspace, workspace_bytes, stream);
 }
 
 extern "C" int spec_accept(const float* logits, const int32_t* tokens, const float* draft_probs,

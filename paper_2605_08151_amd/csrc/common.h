@@ -97,4 +97,85 @@ __device__ inline void lds_dma16(const void* g, void* lds_base)
     asm volatile("global_load_lds_dwordx4 %0, off" ::"v"(g), "{m0}"(m0v) : "memory");
 }
 
+// Block summaries of the large-tile LM head (lm_head_mfma.hip): what acceptance needs from a row of logits without reading it again.  A
+// block is what one wave holds of a row at the end of a pass, at most 64 consecutive vocabulary entries; block index =
+// (panel range * passes per range + pass) * 4 + wave, so blocks cover increasing vocabulary ranges; blk_span[2 b],
+// blk_span[2 b + 1] = first entry and number of entries of block b (0 for a slot that holds nothing).  Per row and block:
+// blk_max = the maximum (NaN if the block holds a NaN) and, for the rows of sampled requests (temperature T > 0),
+// blk_sum = sum of 2^((l - blk_max) log2(e)/T), in fp32.  A row's request is found from qo_indptr once per workgroup.
+struct LmSummary {
+    const float* temperature; // [B]
+    const int32_t* qo_indptr; // [B + 1]
+    int B;
+    float* blk_max;           // [M, blocks]
+    float* blk_sum;           // [M, blocks]
+    int32_t* blk_span;        // [blocks, 2]
+    int blocks, passes_per_range;
+};
+
+
+// Reductions over the four 16-lane rows of a wave (lanes l, l^16, l^32, l^48), result in every lane, with the row-swap
+// instructions of gfx950 instead of two round trips through the LDS crossbar: v_permlane32_swap exchanges the upper half
+// of its first operand with the lower half of the second, v_permlane16_swap the odd rows of the first with the even rows
+// of the second; fed with two copies of x they leave (x_lo, x_lo) / (x_hi, x_hi), resp. rows (0,0,2,2) / (1,1,3,3), whose
+// element-wise combination is the xor-32, resp. xor-16, step of a butterfly.
+// Written as assembly statements: through the compiler's builtins for these two instructions both results of a swap
+// came back as the first one (seen in the generated code: max(first, second) had become a plain copy), so that
+// "the maximum" was that of the first row alone.  The s_nop covers the wait states the instructions need after a
+// vector instruction wrote their operands.
+struct SwapPair { float first, second; };
+
+__device__ inline SwapPair swap_halves(float x)          // (x_lo, x_lo), (x_hi, x_hi)
+{
+    SwapPair p{x, x};
+    asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(p.first), "+v"(p.second));
+    return p;
+}
+
+__device__ inline SwapPair swap_rows(float x)            // rows (0,0,2,2), rows (1,1,3,3)
+{
+    SwapPair p{x, x};
+    asm("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(p.first), "+v"(p.second));
+    return p;
+}
+
+__device__ inline float four_rows_max(float x)
+{
+    const SwapPair a = swap_halves(x);
+    const SwapPair b = swap_rows(fmaxf(a.first, a.second));
+    return fmaxf(b.first, b.second);
+}
+
+__device__ inline float four_rows_sum(float x)
+{
+    const SwapPair a = swap_halves(x);
+    const SwapPair b = swap_rows(a.first + a.second);
+    return b.first + b.second;
+}
+
+// All-reduce over the 16 lanes of a 16-lane row with data-parallel-primitive operand modifiers (rotations by 8, 4, 2, 1
+// within the row): every lane ends with the combination of all 16.  (For a sum the order of the additions differs from
+// lane to lane; callers that need one answer take it from one lane.)
+template <int CTRL>
+__device__ inline float dpp_rotated(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+
+__device__ inline float row16_max(float x)
+{
+    x = fmaxf(x, dpp_rotated<0x128>(x));              // row_ror:8
+    x = fmaxf(x, dpp_rotated<0x124>(x));              // row_ror:4
+    x = fmaxf(x, dpp_rotated<0x122>(x));              // row_ror:2
+    return fmaxf(x, dpp_rotated<0x121>(x));           // row_ror:1
+}
+
+__device__ inline float row16_sum(float x)
+{
+    x += dpp_rotated<0x128>(x);
+    x += dpp_rotated<0x124>(x);
+    x += dpp_rotated<0x122>(x);
+    return x + dpp_rotated<0x121>(x);
+}
+
 }  // namespace specv

@@ -29,10 +29,12 @@ constexpr int kMfPassPanels = kMfWaves * kMfTN;
 constexpr int kMfRing = 4;                     // slabs in flight: hidden slabs in LDS = W slabs in registers
 constexpr int kMfPatchPitch = kMfTN * 64 + 16; // bytes per row of a wave's store patch
 
-template <int TM, bool NT>
+// (SUMMARY instantiations also leave the block summaries described at LmSummary)
+template <int TM, bool NT, bool SUMMARY>
 __global__ __launch_bounds__(64 * kMfWaves, 1) void lm_head_mfma_kernel(
     const uint16_t* __restrict__ A_all, const uint16_t* __restrict__ Wp, float* __restrict__ C_all,
-    int M_all, int H, int V, int n_panels, int panels_per_wg, bool vec_store, int groups, int tiles_lo, int groups_hi)
+    int M_all, int H, int V, int n_panels, int panels_per_wg, bool vec_store, int groups, int tiles_lo, int groups_hi,
+    LmSummary sm)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int RW = kMfRing;
@@ -57,13 +59,39 @@ __global__ __launch_bounds__(64 * kMfWaves, 1) void lm_head_mfma_kernel(
     float* __restrict__ C = C_all + (size_t)row0 * V;
     const int p_begin = range * panels_per_wg;
     const int p_end = min(n_panels, p_begin + panels_per_wg);
-    if (p_begin >= p_end) return;
+    if (p_begin >= p_end) {
+        if constexpr (SUMMARY) {                      // a range past the matrix: its block slots hold nothing
+            if (group == 0)
+                for (int b = tid; b < sm.passes_per_range * kMfWaves; b += 64 * kMfWaves) {
+                    sm.blk_span[2 * (range * sm.passes_per_range * kMfWaves + b)] = 0;
+                    sm.blk_span[2 * (range * sm.passes_per_range * kMfWaves + b) + 1] = 0;
+                }
+        }
+        return;
+    }
     const int n_own = p_end - p_begin;
     const int npass = (n_own + kMfPassPanels - 1) / kMfPassPanels;
     const int nslab = H / kMfSlab;                    // a multiple of 4 (host check)
 
     unsigned char* hbuf = smem;                                        // kMfRing slabs
     unsigned char* patch = smem + kMfRing * kSlabBytes + wave * (16 * kMfPatchPitch);
+    float* row_scale = reinterpret_cast<float*>(smem + kMfRing * kSlabBytes + kMfWaves * (16 * kMfPatchPitch));   // [TM * 16], SUMMARY only
+    if constexpr (SUMMARY) {
+        // log2(e) / T of each row's request (0: greedy, or no such row); read again only after many barriers
+        for (int r = tid; r < TM * 16; r += 64 * kMfWaves) {
+            float sc = 0.0f;
+            if (r < M) {
+                int lo = 0, hi = sm.B - 1;                // largest i with qo_indptr[i] <= row
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (sm.qo_indptr[mid] <= row0 + r) lo = mid; else hi = mid - 1;
+                }
+                const float T = sm.temperature[lo];
+                sc = T > 0.0f ? (float)(1.4426950408889634 / (double)T) : 0.0f;
+            }
+            row_scale[r] = sc;
+        }
+    }
 
     // ---- hidden: byte offset (from A) of the 16 bytes this lane moves in direct load q of a slab, k0 = 0.
     // Load q of wave w fills LDS rows 8 (QN w + q) .. +7: lane l writes position l % 8 of row 8 (QN w + q) + l / 8,
@@ -225,7 +253,15 @@ __global__ __launch_bounds__(64 * kMfWaves, 1) void lm_head_mfma_kernel(
             panel_ptrs(p0n, npn, wnext);
         }
         // acc[tn][tm][i] = C[row 16 tm + l16][entry 16 (st_p0 + tn) + 4 kg + i]
-        if (vec_store) {
+        // (SUMMARY) block of this wave and pass; its span is written once, by the first row group
+        int blk = 0, count = 0;
+        if constexpr (SUMMARY) {
+            blk = (range * sm.passes_per_range + (pass - 1)) * kMfWaves + wave;
+            const int first = st_p0 * 16;
+            count = max(0, min(st_np * 16, V - first));
+            if (group == 0 && lane == 0) { sm.blk_span[2 * blk] = first; sm.blk_span[2 * blk + 1] = count; }
+        }
+        if (vec_store || SUMMARY) {                   // (the summary instantiations are only launched for V % 4 == 0)
             // V % 4 == 0.  The tile is turned through the wave's own LDS patch so that one store instruction writes all
             // the wave's entries of a row (256 bytes), 4 rows at a time.  LDS operations of one wave execute in order, so
             // the patch needs no barrier and no second copy.
@@ -235,17 +271,49 @@ __global__ __launch_bounds__(64 * kMfWaves, 1) void lm_head_mfma_kernel(
             const bool col_ok = scol < st_np * 16 && col0 < V;
             uint32_t off = ((uint32_t)srow * (uint32_t)V + (uint32_t)col0) * 4u;
             const uint32_t row_step = (uint32_t)kRowsPerStore * 4u * (uint32_t)V;
+            // (SUMMARY) running element index of this lane's row in blk_max / blk_sum, stepped like `off`: computed afresh
+            // per row it is invariant from pass to pass, and the compiler would keep all 4 TM of them in registers
+            uint32_t sat = (uint32_t)(row0 + srow) * (uint32_t)sm.blocks + (uint32_t)blk;
+            const uint32_t sat_step = (uint32_t)kRowsPerStore * (uint32_t)sm.blocks;
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
+                f32x4 t[kMfTN];
 #pragma unroll
                 for (int tn = 0; tn < kMfTN; ++tn) {
-                    *reinterpret_cast<f32x4*>(patch + l16 * kMfPatchPitch + (tn * 16 + kg * 4) * 4) = acc[tn][tm];
-                    acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    t[tn] = acc[tn][tm];
+                    *reinterpret_cast<f32x4*>(patch + l16 * kMfPatchPitch + (tn * 16 + kg * 4) * 4) = t[tn];
+                    if constexpr (!SUMMARY) acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
 #pragma unroll
                 for (int q = 0; q < 16 / kRowsPerStore; ++q) {
                     const int prow = q * kRowsPerStore + srow, row = tm * 16 + prow;
                     const f32x4 v = *reinterpret_cast<const f32x4*>(patch + prow * kMfPatchPitch + scol * 4);
+                    if constexpr (SUMMARY) {
+                        // In this layout a row's 64 entries lie in the 16 lanes of one 16-lane row, 4 consecutive entries
+                        // each (the values are in registers for the store anyway; taking them from the accumulators instead
+                        // needs 16 more registers per tile, which this kernel does not have).  Entries past the block do not
+                        // count.  Rotations within the 16-lane row leave the full maximum / sums in every lane.
+                        // scale = log2(e)/T of a sampled row; a greedy row gets 1 so that its sum, which nobody reads as a
+                        // sum, still turns NaN when the block holds a NaN (fmaxf drops NaNs, the exponential does not)
+                        const float rs = row_scale[row];
+                        const float scale = rs > 0.0f ? rs : 1.0f;
+                        const int lim = count - scol;
+                        float x[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) x[e] = e < lim ? v[e] : -INFINITY;
+                        const float m = row16_max(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])));
+                        const float base = m > -INFINITY ? m : 0.0f;
+                        float z = 0.0f;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) z += __builtin_amdgcn_exp2f((x[e] - base) * scale);
+                        z = row16_sum(z);
+                        if ((lane & 15) == 0 && row < M) {
+                            sm.blk_max[sat] = z != z ? z : m;
+                            sm.blk_sum[sat] = rs > 0.0f ? z : 0.0f;
+                        }
+                        sat += sat_step;
+                        asm volatile("" : "+v"(sat));
+                    }
                     if (row < M && col_ok) {
                         f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<unsigned char*>(C) + off);
                         if constexpr (NT) __builtin_nontemporal_store(v, dst); else *dst = v;
@@ -253,10 +321,22 @@ __global__ __launch_bounds__(64 * kMfWaves, 1) void lm_head_mfma_kernel(
                     off += row_step;                  // one running byte offset (rows x V x 4 < 2^32 per group)
                     asm volatile("" : "+v"(off));
                 }
+                // one row tile at a time: left to itself the scheduler interleaves the summaries of all tiles, and their
+                // temporaries (16 values each) no longer fit beside the W ring
+                if constexpr (SUMMARY) __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (SUMMARY) {
+                // the accumulators are cleared only now, behind a fence: cleared tile by tile above, the clears were
+                // moved to the front and every old value had to be copied out (and spilled) first
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < kMfTN; ++tn) acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         } else {
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+            for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
                 for (int tn = 0; tn < kMfTN; ++tn) {
                     const int row = tm * 16 + l16, e = (st_p0 + tn) * 16 + kg * 4;
@@ -267,8 +347,16 @@ __global__ __launch_bounds__(64 * kMfWaves, 1) void lm_head_mfma_kernel(
                     }
                     acc[tn][tm] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
+            }
         }
         if (!more) break;
+    }
+    if constexpr (SUMMARY) {                          // block slots of passes this range does not have
+        if (group == 0)
+            for (int b = npass * kMfWaves + tid; b < sm.passes_per_range * kMfWaves; b += 64 * kMfWaves) {
+                sm.blk_span[2 * (range * sm.passes_per_range * kMfWaves + b)] = 0;
+                sm.blk_span[2 * (range * sm.passes_per_range * kMfWaves + b) + 1] = 0;
+            }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);               // no direct load of this wave is still landing when the LDS is given up
 }
@@ -277,28 +365,14 @@ Tunable g_lm_packed_tile{0};   // benchmark hook: 0 = automatic (this kernel for
 Tunable g_lm_mfma_nt{0};       // benchmark hook: nontemporal logits stores, 0 = automatic (one or two row groups), 1 = always, 2 = never
 Tunable g_lm_mfma_rows{0};     // benchmark hook: rows per group of this kernel at most (144..256), 0 = automatic (208, or the whole batch up to 256)
 
-template <int TM, bool NT>
-static int launch_mfma(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, int groups, int tiles_lo, int groups_hi, hipStream_t s)
-{
-    constexpr int SR = (TM * 16 + 31) / 32 * 32;
-    const size_t smem = (size_t)kMfRing * SR * kMfPitch + (size_t)kMfWaves * 16 * kMfPatchPitch;
-    static LdsGrantTable granted = {};
-    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_mfma_kernel<TM, NT>), smem, granted, "spec_lm_head_packed")) return rc;
-    // panel ranges: as many as there are CUs per row group, a multiple of 8 (one per XCD and step of the dealing)
-    const int cus = device_cu_count();
-    const int n_panels = (V + 15) / 16;
-    const int r0 = max(8, cus / groups / 8 * 8);
-    const int per_range = (n_panels + r0 - 1) / r0;
-    const int ranges = ((n_panels + per_range - 1) / per_range + 7) / 8 * 8;
-    hipLaunchKernelGGL((lm_head_mfma_kernel<TM, NT>), dim3(ranges * groups), dim3(64 * kMfWaves), smem, s, a, wp, c, M, H, V,
-                       n_panels, per_range, V % 4 == 0, groups, tiles_lo, groups_hi);
-    return SPEC_OK;
-}
+// Row groups, panel ranges and the instantiation that serves them (host arithmetic, shared by the launch and by the
+// callers that size the block summaries).
+struct MfmaLayout { int groups, tiles_lo, groups_hi, tm, ranges, per_range, passes_per_range, blocks; bool nt; };
 
-// Row groups and the instantiation that serves them.  Returns SPEC_OK after enqueueing, or a negative status.
-int lm_head_mfma_dispatch(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, hipStream_t s)
+static MfmaLayout mfma_layout(int M, int V)
 {
     constexpr int kMaxTM = 16;
+    MfmaLayout L{};
     // Measured on MI355X (V = 151936, H = 4096): M = 1206 as 6 groups of 12-13 tiles 1314 us, as 5 groups of 15-16 tiles
     // 1346 us (the library GEMM of the image with fp32 output: 1342 us); a batch of at most 16 tiles stays one group.
     const int forced = g_lm_mfma_rows;
@@ -306,22 +380,68 @@ int lm_head_mfma_dispatch(const uint16_t* a, const uint16_t* wp, float* c, int M
     const int cap_tiles = forced >= 16 * 9 && forced <= 16 * kMaxTM ? forced / 16 : (tiles <= kMaxTM ? kMaxTM : 13);
     int groups = (tiles + cap_tiles - 1) / cap_tiles;
     while (groups > 1 && (tiles + groups - 1) / groups < 9) --groups;    // the kernel is built for 9..16 tiles per group
-    const int tiles_lo = tiles / groups, groups_hi = tiles % groups;      // groups of tiles_lo + 1 first, then of tiles_lo
-    const int tm = tiles_lo + (groups_hi ? 1 : 0);
+    L.groups = groups;
+    L.tiles_lo = tiles / groups; L.groups_hi = tiles % groups;           // groups of tiles_lo + 1 first, then of tiles_lo
+    L.tm = L.tiles_lo + (L.groups_hi ? 1 : 0);
     const int nt_forced = g_lm_mfma_nt;
-    const bool nt = nt_forced == 1 || (nt_forced == 0 && groups <= 2);
+    L.nt = nt_forced == 1 || (nt_forced == 0 && groups <= 2);
+    // panel ranges: as many as there are CUs per row group, a multiple of 8 (one per XCD and step of the dealing)
+    const int cus = device_cu_count();
+    const int n_panels = (V + 15) / 16;
+    const int r0 = max(8, cus / groups / 8 * 8);
+    L.per_range = (n_panels + r0 - 1) / r0;
+    L.ranges = ((n_panels + L.per_range - 1) / L.per_range + 7) / 8 * 8;
+    L.passes_per_range = (L.per_range + kMfPassPanels - 1) / kMfPassPanels;
+    L.blocks = L.ranges * L.passes_per_range * kMfWaves;
+    return L;
+}
+
+template <int TM, bool NT, bool SUMMARY>
+static int launch_mfma(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, const MfmaLayout& L, LmSummary sm, hipStream_t s)
+{
+    constexpr int SR = (TM * 16 + 31) / 32 * 32;
+    const size_t smem = (size_t)kMfRing * SR * kMfPitch + (size_t)kMfWaves * 16 * kMfPatchPitch + (SUMMARY ? TM * 16 * 4 : 0);
+    static LdsGrantTable granted = {};
+    if (int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(&lm_head_mfma_kernel<TM, NT, SUMMARY>), smem, granted, "spec_lm_head_packed")) return rc;
+    hipLaunchKernelGGL((lm_head_mfma_kernel<TM, NT, SUMMARY>), dim3(L.ranges * L.groups), dim3(64 * kMfWaves), smem, s, a, wp, c, M, H, V,
+                       (V + 15) / 16, L.per_range, V % 4 == 0, L.groups, L.tiles_lo, L.groups_hi, sm);
+    return SPEC_OK;
+}
+
+// blocks per row of the summaries for this shape; 0 if the large-tile kernel does not take it
+int lm_head_mfma_blocks(int M, int H, int V)
+{
+    // (V % 4 == 0: the summaries are taken while whole rows of the tile are stored; 32-bit element indices)
+    if (M <= 0 || V <= 0 || V % 4 != 0 || H <= 0 || H % (kMfRing * kMfSlab) != 0) return 0;
+    const MfmaLayout L = mfma_layout(M, V);
+    if ((size_t)M * (size_t)L.blocks >= ((size_t)1 << 32)) return 0;
+    return (L.tm >= 9 && L.tm <= 16) ? L.blocks : 0;
+}
+
+// Returns SPEC_OK after enqueueing, or a negative status.  summary == nullptr: logits only.
+int lm_head_mfma_dispatch(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, const LmSummary* summary, hipStream_t s)
+{
+    const MfmaLayout L = mfma_layout(M, V);
     if (H % (kMfRing * kMfSlab) != 0)
         return fail(SPEC_ESHAPE, "spec_lm_head_packed: H=%d must be a multiple of %d", H, kMfRing * kMfSlab);
-    switch (tm) {
+    LmSummary sm{};
+    if (summary) {
+        if (lm_head_mfma_blocks(M, H, V) == 0)
+            return fail(SPEC_ESHAPE, "spec_lm_head_packed_summary: no block summaries for M=%d H=%d V=%d (V must be a multiple of 4)", M, H, V);
+        sm = *summary; sm.blocks = L.blocks; sm.passes_per_range = L.passes_per_range;
+    }
+    switch (L.tm) {
 #define SPECV_MF(TMv)                                                                                             \
         case TMv:                                                                                                 \
-            return nt ? launch_mfma<TMv, true>(a, wp, c, M, H, V, groups, tiles_lo, groups_hi, s)                 \
-                      : launch_mfma<TMv, false>(a, wp, c, M, H, V, groups, tiles_lo, groups_hi, s);
+            if (summary) return L.nt ? launch_mfma<TMv, true, true>(a, wp, c, M, H, V, L, sm, s)                  \
+                                     : launch_mfma<TMv, false, true>(a, wp, c, M, H, V, L, sm, s);                \
+            return L.nt ? launch_mfma<TMv, true, false>(a, wp, c, M, H, V, L, sm, s)                              \
+                        : launch_mfma<TMv, false, false>(a, wp, c, M, H, V, L, sm, s);
         SPECV_MF(9) SPECV_MF(10) SPECV_MF(11) SPECV_MF(12) SPECV_MF(13) SPECV_MF(14) SPECV_MF(15) SPECV_MF(16)
 #undef SPECV_MF
         default: break;
     }
-    return fail(SPEC_ESHAPE, "spec_lm_head_packed: no large-tile instantiation for %d row tiles per group", tm);
+    return fail(SPEC_ESHAPE, "spec_lm_head_packed: no large-tile instantiation for %d row tiles per group", L.tm);
 }
 
 }  // namespace specv

@@ -403,13 +403,14 @@ extern "C" int spec_lm_head_pack(const void* W, void* Wp, int V, int H, void* st
 namespace specv {
 
 extern Tunable g_lm_packed_tile;
-int lm_head_mfma_dispatch(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, hipStream_t s);
+int lm_head_mfma_dispatch(const uint16_t* a, const uint16_t* wp, float* c, int M, int H, int V, const LmSummary* summary, hipStream_t s);
+int lm_head_mfma_blocks(int M, int H, int V);
 
 static int packed_groups(int M) { return (M + kPkMaxRows - 1) / kPkMaxRows; }
 
 // shared by spec_lm_head_packed (blk_max == nullptr) and spec_lm_head_packed_stats
 static int lm_head_packed_any(const char* who, const void* hidden, const void* Wp, float* logits, int M, int H, int V,
-                              float* blk_max, int32_t* blk_arg, void* stream)
+                              float* blk_max, int32_t* blk_arg, void* stream, const LmSummary* summary = nullptr)
 {
     if (M < 0 || H <= 0 || V < 0) return fail(SPEC_EINVAL, "%s: negative size (M=%d H=%d V=%d)", who, M, H, V);
     if (M == 0 || V == 0) return SPEC_OK;
@@ -422,8 +423,10 @@ static int lm_head_packed_any(const char* who, const void* hidden, const void* W
     hipStream_t s = (hipStream_t)stream;
     const uint16_t* wp = (const uint16_t*)Wp;
     // More than 160 rows: the contraction is bound by the matrix cores, and the large-tile kernel serves it
-    if (!blk_max && M > kPkMaxRows && g_lm_packed_tile != 1 && (size_t)V <= ((size_t)1 << 32) / (4 * (size_t)(304 + 16))) {
-        const int rc = lm_head_mfma_dispatch((const uint16_t*)hidden, wp, logits, M, H, V, s);
+    const bool large_tile_fits = M > kPkMaxRows && (size_t)V <= ((size_t)1 << 32) / (4 * (size_t)(304 + 16));
+    if (summary && !large_tile_fits) return fail(SPEC_ESHAPE, "%s: block summaries need more than %d rows (M=%d, V=%d)", who, kPkMaxRows, M, V);
+    if (!blk_max && large_tile_fits && (summary || g_lm_packed_tile != 1)) {
+        const int rc = lm_head_mfma_dispatch((const uint16_t*)hidden, wp, logits, M, H, V, summary, s);
         if (rc != SPEC_OK) return rc;
         return check_launch(who);
     }
@@ -473,6 +476,27 @@ extern "C" int spec_lm_head_packed_stats_blocks(int M, int H, int V)
     int ranges, per_range;
     packed_geometry(V, packed_groups(M), &ranges, &per_range);
     return ranges * ((per_range + 15) / 16);
+}
+
+/* blocks per row of the summaries spec_lm_head_packed_summary writes; 0 = that call does not take this shape */
+extern "C" int spec_lm_head_packed_summary_blocks(int M, int H, int V)
+{
+    using namespace specv;
+    if (M <= kPkMaxRows || (size_t)V > ((size_t)1 << 32) / (4 * (size_t)(304 + 16))) return 0;
+    return lm_head_mfma_blocks(M, H, V);
+}
+
+extern "C" int spec_lm_head_packed_summary(const void* hidden, const void* Wp, float* logits, int M, int H, int V,
+                                           const float* temperature, const int32_t* qo_indptr, int B,
+                                           float* blk_max, float* blk_sum, int32_t* blk_span, void* stream)
+{
+    using namespace specv;
+    if (M > 0 && V > 0 && (!temperature || !qo_indptr || B <= 0 || !blk_max || !blk_sum || !blk_span))
+        return fail(SPEC_EINVAL, "spec_lm_head_packed_summary: NULL pointer argument or B=%d", B);
+    LmSummary sm{};
+    sm.temperature = temperature; sm.qo_indptr = qo_indptr; sm.B = B;
+    sm.blk_max = blk_max; sm.blk_sum = blk_sum; sm.blk_span = blk_span;
+    return lm_head_packed_any("spec_lm_head_packed_summary", hidden, Wp, logits, M, H, V, nullptr, nullptr, stream, &sm);
 }
 
 extern "C" int spec_lm_head_packed_stats(const void* hidden, const void* Wp, float* logits, int M, int H, int V,

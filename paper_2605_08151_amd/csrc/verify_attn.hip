@@ -443,27 +443,11 @@ __global__ __launch_bounds__(NW * 64) void verify_attn_kernel(AttnParams p)
 // of every chunk, and a prologue nobody overlaps: on chunks of ~1000 keys that overhead is as long as the streaming.
 // Here the ROWS are divided instead: wave w owns row tile w (its Q fragments in registers, its softmax state and its
 // 32 accumulator registers) and sees every key of the chunk; the K/V stages (32 keys = two pages of K and of V, 16 KB)
-// are shared by the waves through a ring of four LDS buffers filled by direct global->LDS loads, three stages ahead.
-// A row belongs to one wave, so there is no merge: a wave normalises and stores its own 16 rows.  64 KB of LDS and ~128
-// registers per wave let two workgroups share a CU, so that one's prologue and epilogue hide under the other's stream.
+// are shared by the waves through a ring of two LDS buffers (four is an option) filled by direct global->LDS loads.
+// A row belongs to one wave, so there is no merge: a wave normalises and stores its own 16 rows.  32 KB of LDS and ~100
+// registers per wave let three to four workgroups share a CU, so that one's waits hide under the others' streams.
 // ------------------------------------------------------------------------------------------------
 constexpr int kRowsStageBytes = kWaveLds;      // 32 K rows + 32 V rows
-
-// max over the four 16-lane rows of a wave (the four key groups g of one query row l16), left in every lane, with the
-// row-swap instructions of gfx950 instead of two round trips through the LDS crossbar: v_permlane32_swap exchanges the
-// upper half of its first operand with the lower half of the second, v_permlane16_swap the odd rows of the first with
-// the even rows of the second; fed with two copies of x they leave (x_lo, x_lo) / (x_hi, x_hi), resp. rows (0,0,2,2) /
-// (1,1,3,3), whose element-wise max is the xor-32, resp. xor-16, reduction.
-__device__ inline float across_key_groups_max(float x)
-{
-    typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
-    const unsigned int u = __builtin_bit_cast(unsigned int, x);
-    const u32x2_t a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    x = fmaxf(__builtin_bit_cast(float, a.x), __builtin_bit_cast(float, a.y));
-    const unsigned int v = __builtin_bit_cast(unsigned int, x);
-    const u32x2_t b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-    return fmaxf(__builtin_bit_cast(float, b.x), __builtin_bit_cast(float, b.y));
-}
 
 // RING: K/V stages per workgroup in LDS (RING - 1 of them in flight while one is computed)
 template <int NW, bool FINAL, int RING>
@@ -657,7 +641,7 @@ __global__ __launch_bounds__(NW * 64, (NW <= 5 ? 4 : (NW == 6 ? 3 : 2))) void ve
         float tmax = sc[0];
 #pragma unroll
         for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, sc[e]);
-        tmax = across_key_groups_max(tmax) * scale;       // scale > 0: the maximum of the scaled scores
+        tmax = four_rows_max(tmax) * scale;       // scale > 0: the maximum of the scaled scores
         if (__any(tmax > m_run + kMaxSlack)) {            // lazy reference maximum, as in the kernel above
             const float m_new = fmaxf(m_run, tmax);
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);

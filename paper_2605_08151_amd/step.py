@@ -34,6 +34,22 @@ class VerifyStep:
         self.pblk_max = torch.empty((M, max(1, self.pblocks)), dtype=torch.float32, device=dev)
         self.pblk_arg = torch.empty((M, max(1, self.pblocks)), dtype=torch.int32, device=dev)
 
+        # block summaries of the large-tile packed LM head (more than 160 rows): maxima and sums per block of 64 entries
+        self.sblocks = sv.spec_lm_head_packed_summary_blocks(M, H, V)
+        self.sblk_max = torch.empty((M, max(1, self.sblocks)), dtype=torch.float32, device=dev)
+        self.sblk_sum = torch.empty((M, max(1, self.sblocks)), dtype=torch.float32, device=dev)
+        self.sblk_span = torch.empty((max(1, self.sblocks), 2), dtype=torch.int32, device=dev)
+
+    def lm_head_packed_summary(self, hidden, Wp, temperature, qo_indptr):
+        sv.spec_lm_head_packed_summary(hidden, Wp, self.logits, temperature, qo_indptr, self.sblk_max, self.sblk_sum, self.sblk_span)
+        return self.logits
+
+    def accept_summary(self, tokens, draft_probs, temperature, seeds, round_, qo_indptr):
+        sv.spec_accept_summary(self.logits, tokens, draft_probs, temperature, seeds, round_, qo_indptr, self.accept_len,
+                               self.out_tokens, self.rollback, self.stats, self.gamma_max, self.sblk_max, self.sblk_sum,
+                               self.sblk_span, self.sblocks, self.status, self.accept_ws)
+        return self.accept_len, self.out_tokens
+
     def attn(self, q, k_cache, v_cache, page_table, seq_lens, qo_indptr, scale, want_lse=True):
         sv.spec_verify_attn(q, k_cache, v_cache, page_table, seq_lens, qo_indptr, self.attn_out,
                             self.lse if want_lse else None, self.max_kv_len, self.gamma_max + 1, scale, self.status,

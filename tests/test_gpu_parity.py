@@ -193,6 +193,31 @@ def test_attention_needle_and_causality(sv, oracle):
     _close(out.float().cpu().numpy(), _oracle_attn(oracle, b), "needle")
 
 
+@pytest.mark.parametrize("gammas", [(8,), (0, 2, 4)], ids=["row_split_kernel", "wave_per_key_block_kernel"])
+def test_attention_with_an_overwhelming_key_in_every_key_group(sv, oracle, gammas):
+    """One committed key per request whose score exceeds every other by ~200 in log2 units, at slot 1, 6, 9 or 14 of its
+    page (one of the four groups of keys a 16-lane row of the wave owns): the running maximum has to come from all
+    four groups, or the exponentials overflow.  The output is then that key's value row."""
+    cfg = wl.VerifyConfig("dominant", 17, 8, gammas, ("uniform", 150, 600), 8, 1, 64, 64, sigma_qkv=1.0)
+    b = wl.make_batch(cfg, device="cuda", with_lm_head=False)
+    direction = torch.ones(cfg.D, device="cuda") / math.sqrt(cfg.D)
+    b["q"][:] = (8.0 * direction).to(torch.bfloat16)
+    pt = b["page_table"].cpu()
+    for i, c in enumerate(b["ctx"].tolist()):
+        t = 16 * (3 + i) + (1, 6, 9, 14)[i % 4]             # inside the committed prefix (>= 150 keys): every row sees it
+        page = int(pt[i, t // 16])
+        b["k_cache"][page, 0, t % 16] = (200.0 * direction).to(torch.bfloat16)
+        b["v_cache"][page, 0, t % 16] = 7.0
+    step = _step(b, cfg)
+    out = step.attn(b["q"], b["k_cache"], b["v_cache"], b["page_table"], b["seq_lens"], b["qo_indptr"], b["scale"])
+    torch.cuda.synchronize()
+    o = out.float().cpu().numpy()
+    assert np.isfinite(o).all()
+    np.testing.assert_allclose(o, 7.0, atol=0.05)
+    _close(o, _oracle_attn(oracle, b), "dominant key")
+    assert int(step.status.cpu()) == 0
+
+
 def _split_geometry(length, target):
     """(splits, keys per split) of a request of `length` keys when splits are at most `target` keys long."""
     ns = -(-length // target)
@@ -1167,6 +1192,114 @@ def test_fused_lm_head_statistics(sv, oracle, M, H, V, layout):
         assert (np.diff(ban[r][real]) > 0).all()                                          # blocks cover increasing ranges
     ref = oracle.lm_head(wl.bf16_bits(hidden), wl.bf16_bits(W))
     _close(gl, ref, "fused logits", sharp=True)
+
+
+def _summary_batch(M, B, seed):
+    """qo_indptr of B requests over M rows and a temperature per request (every third greedy)."""
+    rng = np.random.default_rng(seed)
+    cuts = np.sort(rng.choice(np.arange(1, M), B - 1, replace=False))
+    qo = np.concatenate([[0], cuts, [M]]).astype(np.int32)
+    temp = rng.choice([0.5, 0.8, 1.0, 1.3], B).astype(np.float32)
+    temp[::3] = 0.0
+    return qo, temp
+
+
+@pytest.mark.parametrize("M,H,V,sigma", [(300, 256, 5000, 1.0), (161, 256, 151936 // 8 + 4, 1.0), (700, 512, 4100, 3.0),
+                                         (1206, 256, 20012, 1.0), (256, 256, 1016, 1.0)])
+def test_lm_head_block_summaries(sv, oracle, M, H, V, sigma):
+    """spec_lm_head_packed_summary: the logits of spec_lm_head_packed bit for bit; the blocks tile [0, V) in increasing order;
+    every block holds the maximum of its range exactly and, on the rows of sampled requests, the sum of
+    2^((l - max) log2(e)/T) to fp32 accuracy (0 on greedy rows)."""
+    g = torch.Generator(device="cuda").manual_seed(M + V)
+    hidden = (torch.randn((M, H), generator=g, device="cuda") * sigma).to(torch.bfloat16)
+    W = (torch.randn((V, H), generator=g, device="cuda") / math.sqrt(H)).to(torch.bfloat16)
+    W[V // 3] = W[V // 2]                                  # an exact tie between two vocabulary entries
+    B = 24
+    qo, temp = _summary_batch(M, B, M + V)
+    blocks = sv.spec_lm_head_packed_summary_blocks(M, H, V)
+    assert blocks > 0
+    Wp = torch.empty((sv.spec_lm_head_packed_bytes(V, H) // 2,), dtype=torch.bfloat16, device="cuda")
+    sv.spec_lm_head_pack(W, Wp)
+    plain = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    fused = torch.full((M, V), 3.0, dtype=torch.float32, device="cuda")
+    bm = torch.full((M, blocks), 7.0, dtype=torch.float32, device="cuda")
+    bs = torch.full((M, blocks), -7.0, dtype=torch.float32, device="cuda")
+    span = torch.full((blocks, 2), -9, dtype=torch.int32, device="cuda")
+    sv.spec_lm_head_packed(hidden, Wp, plain)
+    sv.spec_lm_head_packed_summary(hidden, Wp, fused, torch.from_numpy(temp).cuda(), torch.from_numpy(qo).cuda(), bm, bs, span)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, fused)
+    gl, bmn, bsn, sp = fused.cpu().numpy().astype(np.float64), bm.cpu().numpy(), bs.cpu().numpy(), span.cpu().numpy()
+    used = sp[:, 1] > 0
+    assert (sp[:, 1] >= 0).all() and (sp[used, 1] <= 64).all()
+    first, count = sp[used, 0], sp[used, 1]
+    assert first[0] == 0 and (first[1:] == first[:-1] + count[:-1]).all() and first[-1] + count[-1] == V   # a partition, in order
+    row_T = np.repeat(temp, np.diff(qo)).astype(np.float64)
+    for b_idx, f, c in zip(np.flatnonzero(used), first, count):
+        seg = gl[:, f:f + c]
+        mx = seg.max(axis=1)
+        np.testing.assert_array_equal(bmn[:, b_idx].astype(np.float64), mx)
+        sampled = row_T > 0
+        want = np.exp2((seg[sampled] - mx[sampled, None]) * (1.4426950408889634 / row_T[sampled, None])).sum(axis=1)
+        np.testing.assert_allclose(bsn[sampled, b_idx], want, rtol=1.0e-5)
+        assert (bsn[~sampled, b_idx] == 0.0).all()
+    _close(gl, oracle.lm_head(wl.bf16_bits(hidden), wl.bf16_bits(W)), "logits beside the summaries", sharp=True)
+
+
+@pytest.mark.parametrize("V,M,sigma", [(5000, 300, 2.0), (20012, 420, 1.0), (151936, 200, 1.0)])
+def test_accept_from_block_summaries_is_bit_exact(sv, oracle, V, M, sigma, accept_filter):
+    """LM head with summaries, then acceptance that never scans a row: integers identical to the oracle's on the same logits,
+    greedy and sampled requests mixed, ties and a NaN row included."""
+    H, B = 256, 40
+    g = torch.Generator(device="cuda").manual_seed(V + M)
+    hidden = (torch.randn((M, H), generator=g, device="cuda") * sigma).to(torch.bfloat16)
+    W = (torch.randn((V, H), generator=g, device="cuda") / math.sqrt(H)).to(torch.bfloat16)
+    W[V // 3] = W[V // 2]
+    rng = np.random.default_rng(V)
+    gammas = rng.integers(0, 9, B)
+    while gammas.sum() + B != M:                           # adjust to exactly M rows
+        k = rng.integers(0, B)
+        gammas[k] += 1 if gammas.sum() + B < M else (-1 if gammas[k] > 0 else 0)
+    qo = _qo(gammas)
+    temp = rng.choice([0.6, 0.9, 1.0], B).astype(np.float32)
+    temp[::2] = 0.0
+    hidden[qo[5] + 1, 7] = float("nan")                     # request 5 (sampled): one poisoned row
+    hidden[qo[8], 3] = float("nan")                         # request 8 (greedy)
+    blocks = sv.spec_lm_head_packed_summary_blocks(M, H, V)
+    Wp = torch.empty((sv.spec_lm_head_packed_bytes(V, H) // 2,), dtype=torch.bfloat16, device="cuda")
+    sv.spec_lm_head_pack(W, Wp)
+    logits = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    bm = torch.empty((M, blocks), dtype=torch.float32, device="cuda")
+    bs = torch.empty((M, blocks), dtype=torch.float32, device="cuda")
+    span = torch.empty((blocks, 2), dtype=torch.int32, device="cuda")
+    temp_d, qo_d = torch.from_numpy(temp).cuda(), torch.from_numpy(qo).cuda()
+    sv.spec_lm_head_packed_summary(hidden, Wp, logits, temp_d, qo_d, bm, bs, span)
+    torch.cuda.synchronize()
+    gl = logits.cpu().numpy()
+    cfg = wl.VerifyConfig("s", V % 977, B, (4,), ("const", 1), 8, 1, 64, V)
+    clean = torch.nan_to_num(logits, nan=0.0)
+    dp, tokens_s = wl.draft_probs_noisy(cfg, qo_d, clean, noise_std=0.7)
+    tokens_g, _ = wl.draft_tokens_greedy(cfg, qo_d, clean.argmax(1).cpu())
+    per_row_T = np.repeat(temp, np.diff(qo))
+    tokens = torch.where(torch.from_numpy(per_row_T > 0), tokens_s, tokens_g).to(torch.int32)
+    seeds = rng.integers(0, 2 ** 63, B, dtype=np.uint64)
+    gmax = int(gammas.max())
+    ws = torch.empty(max(256, sv.spec_accept_workspace_bytes(B, M, V, gmax)), dtype=torch.uint8, device="cuda")
+    al = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    ot = torch.full((B, gmax + 1), -9, dtype=torch.int32, device="cuda")
+    rb = torch.full((B,), 9, dtype=torch.uint8, device="cuda")
+    stats = torch.full((4,), -9, dtype=torch.int32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sv.spec_accept_summary(logits, tokens.cuda(), dp, temp_d, torch.from_numpy(seeds.view(np.int64)).cuda(), 9, qo_d, al, ot, rb,
+                           stats, gmax, bm, bs, span, blocks, status, ws)
+    torch.cuda.synchronize()
+    ref = oracle.accept(gl, tokens.numpy(), dp.cpu().numpy(), temp, seeds, 9, qo, gmax)
+    got = dict(accept_len=al.cpu().numpy(), out_tokens=ot.cpu().numpy(), rollback=rb.cpu().numpy(), stats=stats.cpu().numpy())
+    _assert_same(got, ref, gammas)
+    assert int(status.cpu()) == sv.FLAG_BAD_LOGITS and ref["status"] != 0      # both sides flag the poisoned rows
+    bad = [i for i in range(B) if np.isnan(gl[qo[i]:qo[i + 1]]).any()]
+    assert len(bad) >= 2 and (got["accept_len"][bad] == 0).all() and (got["out_tokens"][bad] == -1).all()
+    assert 0 < ref["accept_len"].sum() < gammas.sum()
 
 
 @pytest.mark.parametrize("layout", ["rowmajor", "packed"])
