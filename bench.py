@@ -567,11 +567,11 @@ def summarize_counters(args):
     with open(md, "w") as o:
         o.write(f"# Verification step, workload '{name}': HBM traffic per launch from rocprofv3 counters\n\n")
         o.write("Commands (on the MI355X box, from the repository root, one counter per run):\n\n")
-        o.write("    cd /tmp && export TMPDIR=/tmp && cd $GRAFT_REPO_ROOT\n")
+        o.write("    cd /tmp && export TMPDIR=/tmp && cd <repository root>; OUT=<a scratch directory>\n")
         for c in ("FETCH_SIZE", "WRITE_SIZE"):
-            o.write(f"    rocprofv3 --pmc {c} --output-format csv -d gpurun_out/pmc_{c} -o {name} -- {cmd}\n")
-        o.write(f"    python3 bench.py --config {name} --summarize-counters gpurun_out/pmc_FETCH_SIZE/{name}_counter_collection.csv "
-                f"gpurun_out/pmc_WRITE_SIZE/{name}_counter_collection.csv\n")
+            o.write(f"    rocprofv3 --pmc {c} --output-format csv -d $OUT/pmc_{c} -o {name} -- {cmd}\n")
+        o.write(f"    python3 bench.py --config {name} --summarize-counters $OUT/pmc_FETCH_SIZE/{name}_counter_collection.csv "
+                f"$OUT/pmc_WRITE_SIZE/{name}_counter_collection.csv\n")
         o.write(f"\nCalibration: the plain 1 GiB device copy of `--copy-probe` (1048576 KiB read, 1048576 KiB written) reads "
                 f"FETCH_SIZE = {pf:.0f} and WRITE_SIZE = {pw:.0f}, so the counters are scaled by {sf:.3f} (fetch) and {sw:.3f} (write) to KiB.\n\n")
         o.write("| kernel | launches | FETCH_SIZE avg | WRITE_SIZE avg | fetched MB | written MB | algorithmic MB | traffic / algorithmic |\n|---|---|---|---|---|---|---|---|\n")
@@ -617,9 +617,9 @@ def summarize_sq(args):
     with open(md, "w") as o:
         o.write(f"# Verification step, workload '{name}': wave, MFMA and LDS counters (rocprofv3 --pmc)\n\n")
         o.write("Commands (on the MI355X box, from the repository root):\n\n")
-        o.write("    cd /tmp && export TMPDIR=/tmp && cd $GRAFT_REPO_ROOT\n")
-        o.write(f"    rocprofv3 --pmc {SQ_COUNTERS} --output-format csv -d gpurun_out/pmc_sq -o {name} -- {cmd}\n")
-        o.write(f"    python3 bench.py --config {name} --summarize-sq gpurun_out/pmc_sq/{name}_counter_collection.csv\n\n")
+        o.write("    cd /tmp && export TMPDIR=/tmp && cd <repository root>; OUT=<a scratch directory>\n")
+        o.write(f"    rocprofv3 --pmc {SQ_COUNTERS} --output-format csv -d $OUT/pmc_sq -o {name} -- {cmd}\n")
+        o.write(f"    python3 bench.py --config {name} --summarize-sq $OUT/pmc_sq/{name}_counter_collection.csv\n\n")
         o.write("Reading: launches of 4 us or more, averages per launch.  GRBM_GUI_ACTIVE is summed over the 8 XCDs (/8 = cycles of the "
                 "launch, 'clock' = cycles / us; it also counts the few microseconds around a dispatch, so the clock of a short kernel reads "
                 "high).  SQ_VALU_MFMA_BUSY_CYCLES is summed over the 1024 SIMDs; one MFMA MOP is 512 flop.  VALU / wait columns are "
@@ -636,7 +636,7 @@ def write_peaks_md(path, rec):
     p = rec["measured_peaks"]
     with open(path, "w") as o:
         o.write("# Measured ceilings of the MI355X box (probes of the library, HIP events on the launch stream)\n\n")
-        o.write("Command (on the MI355X box, from the repository root):\n\n    python3 bench.py --peaks --peaks-md gpurun_out/peaks.md\n\n")
+        o.write("Command (on the MI355X box, from the repository root; OUT = a scratch directory):\n\n    python3 bench.py --peaks --peaks-md $OUT/peaks.md\n\n")
         o.write("| probe | measured | datasheet | ratio |\n|---|---|---|---|\n")
         hb, mf = rec["datasheet"]["hbm_GBs"], rec["datasheet"]["mfma_bf16_TFLOPs"]
         o.write(f"| linear read of 2 GiB (`spec_probe_read`, 16-byte loads, 4 KB per workgroup step), median | {p['hbm_linear_read_GBs']:.0f} GB/s | {hb:.0f} GB/s | {p['hbm_linear_read_GBs'] / hb:.3f} |\n")
@@ -660,9 +660,9 @@ def summarize_trace(args):
     with open(md, "w") as o:
         o.write(f"# Verification step, workload '{name}': rocprofv3 kernel trace\n\n")
         o.write("Command (on the MI355X box, from the repository root):\n\n")
-        o.write(f"    cd /tmp && export TMPDIR=/tmp && cd $GRAFT_REPO_ROOT && rocprofv3 --kernel-trace --stats --output-format csv "
-                f"-d gpurun_out/prof -o {name} -- {cmd}\n")
-        o.write(f"    python3 bench.py --config {name} --summarize-trace gpurun_out/prof/{name}_kernel_stats.csv\n\n")
+        o.write(f"    OUT=<a scratch directory>; cd /tmp && export TMPDIR=/tmp && cd <repository root> && rocprofv3 --kernel-trace --stats --output-format csv "
+                f"-d $OUT/prof -o {name} -- {cmd}\n")
+        o.write(f"    python3 bench.py --config {name} --summarize-trace $OUT/prof/{name}_kernel_stats.csv\n\n")
         o.write("Kernel-trace statistics of the library's kernels (durations in microseconds):\n\n")
         o.write("| kernel | calls | avg us | min us | max us | stddev us |\n|---|---|---|---|---|---|\n")
         for r in rows:
