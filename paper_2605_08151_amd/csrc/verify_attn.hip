@@ -1152,7 +1152,7 @@ extern "C" int spec_verify_attn_tree(const void* q, const void* k_cache, const v
     if (rc != SPEC_OK) return rc;
     if (p.splits == 1) return SPEC_OK;                    // the main kernel wrote the output itself
     // few pieces per request (typical count in work-list mode: items per request): one workgroup per row
-    const bool few = pc.on ? (pc.target_items + B) / B <= 8 : p.splits <= 8;
+    const bool few = pc.on ? (pc.target_items + B) / B <= 8 : p.splits <= 16;
     if (few) hipLaunchKernelGGL(verify_attn_combine_rows_kernel, dim3(M), dim3(256), 0, s, p, B);
     else hipLaunchKernelGGL(verify_attn_combine_kernel, dim3(M, Hq), dim3(256), 0, s, p, B);
     return check_launch("spec_verify_attn (combine)");
