@@ -1545,6 +1545,19 @@ def test_full_size_hybrid_mix_properties(sv, oracle):
     assert np.array_equal(step.accept_len.cpu().numpy(), ref["accept_len"])
     assert np.array_equal(step.out_tokens.cpu().numpy(), ref["out_tokens"])
     assert np.array_equal(step.rollback.cpu().numpy(), ref["rollback"])
+    # the same batch through the LM head that leaves block summaries and the acceptance that scans no logits
+    Wp = step.pack_weights(b["W"])
+    kept = step.logits.clone()
+    step.logits.zero_()
+    step.lm_head_packed_summary(b["hidden"], Wp, b["temperature"], b["qo_indptr"])
+    assert torch.equal(step.logits, kept)
+    step.accept_len.fill_(-7); step.out_tokens.fill_(-7); step.rollback.fill_(7)
+    step.accept_summary(tokens.cuda(), dp, b["temperature"], b["seeds"], 2, b["qo_indptr"])
+    torch.cuda.synchronize()
+    assert np.array_equal(step.accept_len.cpu().numpy(), ref["accept_len"])
+    assert np.array_equal(step.out_tokens.cpu().numpy(), ref["out_tokens"])
+    assert np.array_equal(step.rollback.cpu().numpy(), ref["rollback"])
+    assert int(step.status.cpu()) == 0
     # gamma = 0 requests (the padded parallel-mode candidates) emit exactly one token and never roll back
     g0 = b["gammas"].numpy() == 0
     assert (ref["accept_len"][g0] == 0).all() and (ref["rollback"][g0] == 0).all() and (ref["out_tokens"][g0, 0] >= 0).all()
